@@ -1,0 +1,116 @@
+/*
+ * gemm.h -- C ABI of the MI355X (gfx950) dense matrix-multiplication library.
+ *
+ * The operation is the paper's MatMul specification (Section 3.1,
+ * "Specifications"): three matrices in global memory, each with a shape, an
+ * element type and a storage layout,
+ *
+ *      A : M x K        B : K x N        C : M x N
+ *      C(i,j) = sum_{k=0..K-1} A(i,k) * B(k,j)
+ *
+ * C is OVERWRITTEN (Section 3.2, "Epilog": the accumulator is zero-filled and
+ * then stored); there is no alpha/beta and no accumulate-into-C.
+ *
+ * Pointers
+ *   Every matrix pointer is a DEVICE pointer owned by the caller.  The library
+ *   neither frees nor retains them.  C must not overlap A or B.
+ *
+ * Layout and leading dimension
+ *   layout is GEMM_ROW_MAJOR or GEMM_COL_MAJOR, given per operand.  Element
+ *   (r,c) of a row-major matrix is at index r*ld + c, of a column-major matrix
+ *   at r + c*ld (indices in elements).  ld == 0 means packed (row-major: number
+ *   of columns, column-major: number of rows); otherwise ld must be at least
+ *   that value.  Elements between the packed extent and ld are never read or
+ *   written.  Pointers need only element alignment; 16-byte aligned bases with
+ *   leading dimensions that are multiples of 16 bytes take the fastest kernels.
+ *
+ * Element types
+ *   gemm_f32    : binary32 operands, IEEE binary32 multiply-add, binary32 C.
+ *   gemm_f16f32 : binary16 operands (passed as their 16-bit patterns), products
+ *                 accumulated in binary32, binary32 C.
+ *   The order in which the K products are added is unspecified.
+ *
+ * Execution
+ *   Work is enqueued on hip_stream (a hipStream_t cast to void*; NULL is the
+ *   default stream) of the current device.  The call does not synchronise with
+ *   the host.  Shapes that are split along K use a per-device workspace that
+ *   the library grows with hipMalloc on demand and frees in gemm_shutdown();
+ *   calls issued concurrently on different streams of one device must not both
+ *   need the workspace.
+ *
+ * Sizes
+ *   M, N, K >= 0 and each below 2^31 - 256.  M == 0 or N == 0: nothing is
+ *   done.  K == 0: C is filled with zeros (empty sum).
+ *
+ * Errors
+ *   Functions return GEMM_OK (0) or a negative gemm_status_t; they never abort
+ *   or throw.  Nothing is enqueued when a negative value is returned from
+ *   argument validation.
+ */
+#ifndef MI355X_GEMM_H
+#define MI355X_GEMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { GEMM_ROW_MAJOR = 0, GEMM_COL_MAJOR = 1 } gemm_layout_t;
+
+typedef enum {
+    GEMM_OK = 0,
+    GEMM_ERR_INVALID_ARG = -1, /* negative size, bad layout, small ld, null pointer */
+    GEMM_ERR_HIP = -2,         /* a HIP runtime call or the kernel launch failed */
+    GEMM_ERR_UNSUPPORTED = -3, /* size beyond the stated limits, unknown forced config */
+    GEMM_ERR_WORKSPACE = -4    /* the split-K workspace could not be allocated */
+} gemm_status_t;
+
+/* C = A*B, binary32 throughout (paper Section 3.1, MatMul with float elements). */
+int gemm_f32(int64_t M, int64_t N, int64_t K,
+             const float *A, int layoutA, int64_t lda,
+             const float *B, int layoutB, int64_t ldb,
+             float *C, int layoutC, int64_t ldc,
+             void *hip_stream);
+
+/*
+ * C = A*B, binary16 operands, binary32 accumulation and result (the mixed
+ * precision of the paper's Tensor Core kernels, Section 4.2, with the
+ * accumulator kept in binary32).
+ */
+int gemm_f16f32(int64_t M, int64_t N, int64_t K,
+                const uint16_t *A, int layoutA, int64_t lda,
+                const uint16_t *B, int layoutB, int64_t ldb,
+                float *C, int layoutC, int64_t ldc,
+                void *hip_stream);
+
+/*
+ * Kernel-configuration control (the paper tunes the block tile per input size,
+ * Section 5.3; here a heuristic picks it and this hook overrides it).
+ * name is "auto" / NULL for the heuristic, or "<tile>" or "<tile>:s<splits>",
+ * e.g. "t256x256", "t128x128:s4".  Returns GEMM_ERR_UNSUPPORTED for an unknown
+ * name.  The setting is process-wide.
+ */
+int gemm_force_config(const char *name);
+
+/* Number of tile configurations, and the name of the i-th (NULL if out of range). */
+int gemm_num_configs(void);
+const char *gemm_config_name(int i);
+
+/*
+ * Description of the configuration the last successful call on this thread
+ * used, e.g. "f16 t256x256 NT aligned s1".  The string is thread-local storage
+ * owned by the library, valid until the thread's next gemm call.
+ */
+const char *gemm_last_config(void);
+
+/* Text for a status code (static storage). */
+const char *gemm_status_string(int status);
+
+/* Frees the per-device workspaces.  Safe to call more than once. */
+int gemm_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355X_GEMM_H */

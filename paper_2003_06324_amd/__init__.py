@@ -1,0 +1,12 @@
+"""MI355X-native dense GEMM (C = A*B): thin Python binding of the C-ABI library.
+
+Everything is computed by the HIP kernels in csrc/; this package only loads
+libgemm_mi355x.so and marshals arguments.  There is no CPU fallback: if the
+library cannot be loaded, calls raise.
+"""
+from .gemm import (COL_MAJOR, ROW_MAJOR, GemmError, config_names, force_config, gemm_f16f32,
+                   gemm_f32, last_config, library_path, load_library, shutdown, status_string)
+
+__all__ = ["ROW_MAJOR", "COL_MAJOR", "GemmError", "gemm_f32", "gemm_f16f32", "force_config",
+           "config_names", "last_config", "status_string", "shutdown", "load_library",
+           "library_path"]

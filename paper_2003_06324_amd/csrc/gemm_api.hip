@@ -1,0 +1,334 @@
+// C ABI of the library: argument validation, per-shape tile / split-K
+// selection (the paper picks the block tile per input size, Section 5.3), and
+// kernel launches on the caller's stream.  No host synchronisation.
+#include "gemm.h"
+#include "gemm_launch.h"
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+
+using namespace gemm_gfx950;
+
+namespace gemm_gfx950 {
+GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 128, 128, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 64, 64, 2, 2)
+GEMM_DECLARE_TILE(float, 256, 256, 2, 2)
+GEMM_DECLARE_TILE(float, 128, 128, 2, 2)
+GEMM_DECLARE_TILE(float, 64, 64, 2, 2)
+}  // namespace gemm_gfx950
+
+namespace {
+
+// Sums the K-slices of the workspace in slice order (deterministic) into C.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int64_t split_stride,
+                                                            int splits, float *C, int64_t ldc,
+                                                            int M, int N)
+{
+    const int64_t total = (int64_t)M * N;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * 256) {
+        float s = 0.0f;
+        for (int z = 0; z < splits; ++z) s += ws[z * split_stride + idx];
+        const int64_t r = idx / N, c = idx - r * N;
+        C[r * ldc + c] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *C, int64_t ldc, int M, int N)
+{
+    const int64_t total = (int64_t)M * N;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * 256) {
+        const int64_t r = idx / N, c = idx - r * N;
+        C[r * ldc + c] = 0.0f;
+    }
+}
+
+constexpr int NUM_CU = 256;
+
+struct TileConfig {
+    const char *name;
+    int BM, BN;
+    int wg_per_cu;     // resident workgroups per CU (LDS-limited)
+    double rate;       // relative MFMA efficiency of the steady-state loop
+    launch_fn f16, f32;
+};
+
+const TileConfig kTiles[] = {
+    {"t256x256", 256, 256, 1, 1.00, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
+    {"t128x128", 128, 128, 2, 0.70, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
+    {"t64x64", 64, 64, 4, 0.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+std::mutex g_mutex;
+int g_forced_tile = -1;    // -1: heuristic
+int g_forced_splits = 0;   // 0: heuristic
+struct Workspace { void *ptr = nullptr; size_t bytes = 0; };
+std::map<int, Workspace> g_workspace;
+
+thread_local char t_last_config[128] = "none";
+
+int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Rough cost of running (tile, splits) in units of "one CU doing one
+// 256x256x(BK) step at full rate"; only the ordering between candidates matters.
+double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t KT, int splits, bool f32)
+{
+    const int64_t tiles = cdiv(M, t.BM) * cdiv(N, t.BN);
+    const int64_t kt_slice = cdiv(KT, splits);
+    const double slots = (double)NUM_CU * t.wg_per_cu;
+    const double rounds = (double)cdiv(tiles * splits, (int64_t)slots);
+    // a workgroup's time: its MFMA work at the tile's rate, slowed down by sharing the CU
+    const double step = (double)t.BM * t.BN / (256.0 * 256.0) / t.rate;
+    const double prologue = f32 ? 1.0 : 6.0;  // fill latency + epilogue, in 256x256 steps
+    double cost = rounds * t.wg_per_cu * (step * (double)kt_slice + prologue * step + 1.0);
+    if (splits > 1) {
+        // workspace write + read + final write against ~4 TB/s, plus a second launch,
+        // converted to steps (one f16 step ~0.85 us, one f32 step ~6.8 us at full rate)
+        const double bytes = (double)M * N * 4.0 * (2.0 * splits + 1.0);
+        const double step_us = f32 ? 6.8 : 0.85;
+        cost += (bytes / 4.0e6 + 4.0) / step_us;
+    }
+    return cost;
+}
+
+void choose(int64_t M, int64_t N, int64_t KT, bool f32, int &tile, int &splits)
+{
+    double best = 1e300;
+    tile = g_forced_tile >= 0 ? g_forced_tile : 0;
+    splits = 1;
+    for (int t = 0; t < kNumTiles; ++t) {
+        if (g_forced_tile >= 0 && t != g_forced_tile) continue;
+        for (int s = 1; s <= 64; s *= 2) {
+            const int cand = g_forced_splits > 0 ? g_forced_splits : s;
+            if (cand > 1 && cand > KT) break;
+            const double c = estimate_cost(kTiles[t], M, N, KT, cand, f32);
+            if (c < best) { best = c; tile = t; splits = cand; }
+            if (g_forced_splits > 0) break;
+        }
+    }
+    if (g_forced_splits > 0) splits = (int)(g_forced_splits < KT ? g_forced_splits : KT);
+}
+
+bool bad_matrix(const void *p, int layout, int64_t &ld, int64_t rows, int64_t cols)
+{
+    if (layout != GEMM_ROW_MAJOR && layout != GEMM_COL_MAJOR) return true;
+    const int64_t packed = layout == GEMM_ROW_MAJOR ? cols : rows;
+    if (ld == 0) ld = packed;
+    if (ld < packed) return true;
+    if (rows > 0 && cols > 0 && p == nullptr) return true;
+    return false;
+}
+
+int get_workspace(size_t bytes, void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return GEMM_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Workspace &w = g_workspace[dev];
+    if (w.bytes < bytes) {
+        if (w.ptr) {
+            // earlier launches may still be reading the old buffer
+            if (hipDeviceSynchronize() != hipSuccess) return GEMM_ERR_HIP;
+            (void)hipFree(w.ptr);
+            w.ptr = nullptr;
+            w.bytes = 0;
+        }
+        void *p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return GEMM_ERR_WORKSPACE;
+        }
+        w.ptr = p;
+        w.bytes = bytes;
+    }
+    *out = w.ptr;
+    return GEMM_OK;
+}
+
+template <typename T>
+int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t lda,
+              const void *B, int layB, int64_t ldb, float *C, int layC, int64_t ldc, void *stream_)
+{
+    constexpr bool f32 = sizeof(T) == 4;
+    constexpr int64_t kMax = 2147483647LL - 256;
+    if (M < 0 || N < 0 || K < 0) return GEMM_ERR_INVALID_ARG;
+    if (lda < 0 || ldb < 0 || ldc < 0) return GEMM_ERR_INVALID_ARG;
+    if (bad_matrix(A, layA, lda, M, K) || bad_matrix(B, layB, ldb, K, N) || bad_matrix(C, layC, ldc, M, N))
+        return GEMM_ERR_INVALID_ARG;
+    if (M > kMax || N > kMax || K > kMax) return GEMM_ERR_UNSUPPORTED;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (M == 0 || N == 0) {
+        snprintf(t_last_config, sizeof t_last_config, "%s empty", f32 ? "f32" : "f16");
+        return GEMM_OK;
+    }
+
+    // A column-major C is the row-major N x M matrix C^T = B^T * A^T; a
+    // transposed operand is the same buffer with the other layout flag.
+    if (layC == GEMM_COL_MAJOR) {
+        std::swap(A, B);
+        std::swap(lda, ldb);
+        const int la = layB ^ 1, lb = layA ^ 1;
+        layA = la;
+        layB = lb;
+        std::swap(M, N);
+        layC = GEMM_ROW_MAJOR;
+    }
+
+    if (K == 0) {
+        const int64_t total = M * N;
+        const int blocks = (int)(cdiv(total, 256) < 65536 ? cdiv(total, 256) : 65536);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, (int)M, (int)N);
+        if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
+        snprintf(t_last_config, sizeof t_last_config, "%s zero-fill", f32 ? "f32" : "f16");
+        return GEMM_OK;
+    }
+
+    const bool akc = layA == GEMM_ROW_MAJOR;  // A(i,k) contiguous in k
+    const bool bkc = layB == GEMM_COL_MAJOR;  // B(k,j) contiguous in k
+    constexpr int EPC = Elem<T>::EPC, BK = Elem<T>::BK;
+    bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && (lda % EPC == 0) && (ldb % EPC == 0);
+    if (!akc && M % EPC != 0) aligned = false;
+    if (!bkc && N % EPC != 0) aligned = false;
+
+    const int64_t KT = cdiv(K, BK);
+    int tile, splits;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        choose(M, N, KT, f32, tile, splits);
+    }
+    const TileConfig &t = kTiles[tile];
+    const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
+    if (tiles_m * tiles_n > (1LL << 28)) return GEMM_ERR_UNSUPPORTED;
+    int64_t kt_per_split = cdiv(KT, splits);
+    splits = (int)cdiv(KT, kt_per_split);  // no empty slices
+
+    KernelArgs a;
+    a.A = A;
+    a.B = B;
+    a.lda = lda;
+    a.ldb = ldb;
+    a.M = (int)M;
+    a.N = (int)N;
+    a.K = (int)K;
+    a.tiles_m = (int)tiles_m;
+    a.tiles_n = (int)tiles_n;
+    a.kt_per_split = (int)kt_per_split;
+    void *ws = nullptr;
+    if (splits > 1) {
+        const int rc = get_workspace((size_t)splits * (size_t)M * (size_t)N * sizeof(float), &ws);
+        if (rc != GEMM_OK) return rc;
+        a.C = (float *)ws;
+        a.ldc = N;
+        a.split_stride = M * N;
+    } else {
+        a.C = C;
+        a.ldc = ldc;
+        a.split_stride = 0;
+    }
+    const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n, 8)), (unsigned)splits);
+    const launch_fn fn = f32 ? t.f32 : t.f16;
+    if (fn(akc, bkc, aligned, grid, stream, a) != hipSuccess) return GEMM_ERR_HIP;
+    if (splits > 1) {
+        const int64_t total = M * N;
+        const int blocks = (int)(cdiv(total, 256) < 4096 ? cdiv(total, 256) : 4096);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws,
+                           (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
+        if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
+    }
+    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d", f32 ? "f32" : "f16", t.name,
+             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits);
+    return GEMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int layoutA, int64_t lda,
+             const float *B, int layoutB, int64_t ldb, float *C, int layoutC, int64_t ldc, void *hip_stream)
+{
+    return gemm_impl<float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
+}
+
+int gemm_f16f32(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA, int64_t lda,
+                const uint16_t *B, int layoutB, int64_t ldb, float *C, int layoutC, int64_t ldc,
+                void *hip_stream)
+{
+    return gemm_impl<_Float16>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
+}
+
+int gemm_force_config(const char *name)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (name == nullptr || strcmp(name, "auto") == 0 || name[0] == 0) {
+        g_forced_tile = -1;
+        g_forced_splits = 0;
+        return GEMM_OK;
+    }
+    std::string s(name);
+    int splits = 0;
+    const size_t colon = s.find(':');
+    if (colon != std::string::npos) {
+        const std::string tail = s.substr(colon + 1);
+        if (tail.size() < 2 || tail[0] != 's') return GEMM_ERR_UNSUPPORTED;
+        char *end = nullptr;
+        const long v = strtol(tail.c_str() + 1, &end, 10);
+        if (*end != 0 || v < 1 || v > 1024) return GEMM_ERR_UNSUPPORTED;
+        splits = (int)v;
+        s = s.substr(0, colon);
+    }
+    int tile = -1;
+    if (s == "auto") {
+        tile = -1;
+    } else {
+        for (int i = 0; i < kNumTiles; ++i)
+            if (s == kTiles[i].name) tile = i;
+        if (tile < 0) return GEMM_ERR_UNSUPPORTED;
+    }
+    g_forced_tile = tile;
+    g_forced_splits = splits;
+    return GEMM_OK;
+}
+
+int gemm_num_configs(void) { return kNumTiles; }
+
+const char *gemm_config_name(int i) { return (i >= 0 && i < kNumTiles) ? kTiles[i].name : nullptr; }
+
+const char *gemm_last_config(void) { return t_last_config; }
+
+const char *gemm_status_string(int status)
+{
+    switch (status) {
+    case GEMM_OK: return "ok";
+    case GEMM_ERR_INVALID_ARG: return "invalid argument";
+    case GEMM_ERR_HIP: return "HIP runtime or launch failure";
+    case GEMM_ERR_UNSUPPORTED: return "unsupported size or configuration";
+    case GEMM_ERR_WORKSPACE: return "split-K workspace allocation failed";
+    default: return "unknown status";
+    }
+}
+
+int gemm_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int rc = GEMM_OK;
+    for (auto &kv : g_workspace) {
+        if (kv.second.ptr) {
+            int cur = 0;
+            (void)hipGetDevice(&cur);
+            if (hipSetDevice(kv.first) != hipSuccess || hipFree(kv.second.ptr) != hipSuccess) rc = GEMM_ERR_HIP;
+            (void)hipSetDevice(cur);
+        }
+    }
+    g_workspace.clear();
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Host-side launcher shared by the per-tile instantiation files: maps the
+// run-time (layout, alignment) choice onto the kernel template's booleans.
+#pragma once
+#include "gemm_kernel.h"
+
+namespace gemm_gfx950 {
+
+template <typename T, int BM, int BN, int WM, int WN, bool AKC, bool BKC>
+static hipError_t launch_aligned(bool aligned, dim3 grid, hipStream_t s, const KernelArgs &a)
+{
+    const dim3 block(WM * WN * 64);
+    if (aligned)
+        hipLaunchKernelGGL((gemm_tile_kernel<T, BM, BN, WM, WN, AKC, BKC, true>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((gemm_tile_kernel<T, BM, BN, WM, WN, AKC, BKC, false>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+// akc: A is K-contiguous (row-major); bkc: B is K-contiguous (column-major)
+template <typename T, int BM, int BN, int WM, int WN>
+hipError_t launch_tile(bool akc, bool bkc, bool aligned, dim3 grid, hipStream_t s, const KernelArgs &a)
+{
+    if (akc && bkc) return launch_aligned<T, BM, BN, WM, WN, true, true>(aligned, grid, s, a);
+    if (akc && !bkc) return launch_aligned<T, BM, BN, WM, WN, true, false>(aligned, grid, s, a);
+    if (!akc && bkc) return launch_aligned<T, BM, BN, WM, WN, false, true>(aligned, grid, s, a);
+    return launch_aligned<T, BM, BN, WM, WN, false, false>(aligned, grid, s, a);
+}
+
+typedef hipError_t (*launch_fn)(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
+
+#define GEMM_DECLARE_TILE(T, BM, BN, WM, WN) \
+    extern template hipError_t launch_tile<T, BM, BN, WM, WN>(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
+#define GEMM_INSTANTIATE_TILE(T, BM, BN, WM, WN) \
+    template hipError_t launch_tile<T, BM, BN, WM, WN>(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
+
+}  // namespace gemm_gfx950

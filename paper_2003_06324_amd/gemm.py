@@ -1,0 +1,109 @@
+"""ctypes binding of include/gemm.h.  Argument marshalling only.
+
+The functions take raw device addresses (ints), or any object exposing
+``data_ptr()`` (a torch tensor) -- torch is used by callers purely to own
+device memory and streams.  Names and argument order follow the C header.
+"""
+import ctypes
+import os
+
+ROW_MAJOR = 0
+COL_MAJOR = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
+_lib = None
+
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_force_config", "gemm_num_configs", "gemm_config_name",
+           "gemm_last_config", "gemm_status_string", "gemm_shutdown")
+
+
+class GemmError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("gemm call failed: %s (status %d)" % (text, status))
+        self.status = status
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libgemm_mi355x.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    sig = [i64, i64, i64, p, i32, i64, p, i32, i64, p, i32, i64, p]
+    for name in ("gemm_f32", "gemm_f16f32"):
+        fn = getattr(lib, name)
+        fn.argtypes = sig
+        fn.restype = i32
+    lib.gemm_force_config.argtypes = [ctypes.c_char_p]
+    lib.gemm_force_config.restype = i32
+    lib.gemm_num_configs.argtypes = []
+    lib.gemm_num_configs.restype = i32
+    lib.gemm_config_name.argtypes = [i32]
+    lib.gemm_config_name.restype = ctypes.c_char_p
+    lib.gemm_last_config.argtypes = []
+    lib.gemm_last_config.restype = ctypes.c_char_p
+    lib.gemm_status_string.argtypes = [i32]
+    lib.gemm_status_string.restype = ctypes.c_char_p
+    lib.gemm_shutdown.argtypes = []
+    lib.gemm_shutdown.restype = i32
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr() or None
+    return int(x) or None
+
+
+def status_string(status):
+    return load_library().gemm_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise GemmError(status, status_string(status))
+    return status
+
+
+def gemm_f32(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stream=None, check=True):
+    """C = A*B, binary32. A, B, C: device addresses or tensors; stream: hipStream_t as int."""
+    rc = load_library().gemm_f32(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
+                                 _ptr(C), layoutC, ldc, stream or None)
+    return _check(rc) if check else rc
+
+
+def gemm_f16f32(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stream=None, check=True):
+    """C = A*B, binary16 operands, binary32 accumulation and result."""
+    rc = load_library().gemm_f16f32(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
+                                    _ptr(C), layoutC, ldc, stream or None)
+    return _check(rc) if check else rc
+
+
+def force_config(name=None, check=True):
+    rc = load_library().gemm_force_config(name.encode() if name else None)
+    return _check(rc) if check else rc
+
+
+def config_names():
+    lib = load_library()
+    return [lib.gemm_config_name(i).decode() for i in range(lib.gemm_num_configs())]
+
+
+def last_config():
+    return load_library().gemm_last_config().decode()
+
+
+def shutdown():
+    return _check(load_library().gemm_shutdown())

@@ -1,0 +1,138 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element,
+on seeded inputs.  Floating-point bar: max|C-Cref| / (K max|A| max|B|) <= 1e-6 (f32),
+<= 2e-4 (f16 operands, f32 accumulation); integer-valued inputs must match bit for bit."""
+import itertools
+
+import numpy as np
+import pytest
+
+import gemm_inputs as gi
+from gpu_util import check, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+LAYS = (gi.ROW_MAJOR, gi.COL_MAJOR)
+LAYOUT_PAIRS = list(itertools.product(LAYS, repeat=2))
+TILES = ["t256x256", "t128x128", "t64x64"]
+
+# several tiles of every configuration plus ragged tails in every dimension
+SHAPES = [(256, 256, 256), (300, 200, 100), (129, 257, 65), (513, 383, 130), (64, 72, 520),
+          (1, 1, 1), (7, 5, 3), (33, 1, 77), (1, 300, 64)]
+
+
+def ref_of(oracle, A, B, dtype):
+    M, K = A.shape
+    return oracle.gemm(M, B.shape[1], K, A, gi.ROW_MAJOR, B, gi.ROW_MAJOR, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_random_all_layouts(oracle, dtype, shape):
+    M, N, K = shape
+    A, B = gi.make_problem(100 + M + N + K, M, N, K, "uniform", dtype)
+    ref = ref_of(oracle, A, B, dtype)
+    for la, lb in LAYOUT_PAIRS:
+        C = run_gpu(dtype, A, B, la, lb)
+        check(C, ref, A, B, dtype, "%s %s la=%d lb=%d" % (dtype, shape, la, lb))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("tile", TILES)
+def test_integer_bit_exact_every_tile(oracle, dtype, tile):
+    # entries in {-4..4}: every partial sum is an exact integer below 2^24, so any
+    # summation order gives the same binary32 result and equality must be exact
+    for (M, N, K) in [(300, 260, 200), (257, 129, 67), (512, 512, 192)]:
+        A, B = gi.make_problem(7 + M, M, N, K, "int", dtype)
+        ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for la, lb in LAYOUT_PAIRS:
+            for splits in (1, 3):
+                C, cfg = run_gpu(dtype, A, B, la, lb, force="%s:s%d" % (tile, splits), return_config=True)
+                assert tile in cfg
+                assert np.array_equal(C, ref), (dtype, tile, M, N, K, la, lb, splits, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_k_loop_lengths(oracle, dtype):
+    # every K-loop trip count from a lone partial chunk to three chunks and a tail,
+    # on aligned and unaligned leading dimensions (double-buffer hand-over)
+    bk = 64 if dtype == "f16" else 32
+    ks = [1, 2, 7, 8, bk - 1, bk, bk + 1, bk + 8, 2 * bk, 2 * bk + 8, 3 * bk, 3 * bk + 1, 3 * bk + 16]
+    for K in ks:
+        A, B = gi.make_problem(900 + K, 136, 72, K, "int", dtype)
+        ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for la, lb in LAYOUT_PAIRS:
+            for tile in ("t128x128", "t64x64"):
+                C = run_gpu(dtype, A, B, la, lb, force=tile)
+                assert np.array_equal(C, ref), (dtype, K, la, lb, tile)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_column_major_c_padding_and_offsets(oracle, dtype):
+    A, B = gi.make_problem(31, 200, 168, 144, "int", dtype)
+    ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+    epc = 8 if dtype == "f16" else 4
+    for la, lb, lc in itertools.product(LAYS, repeat=3):
+        # aligned padding keeps the direct-load kernels, odd padding / offsets force the guarded ones
+        for pads, offs in (((epc, 2 * epc, 3), (0, 0, 0)), ((1, 3, 5), (0, 0, 0)), ((0, 0, 0), (1, 3, 1)),
+                           ((epc, epc, 0), (epc, 2 * epc, 2))):
+            C, cfg = run_gpu(dtype, A, B, la, lb, lc, pads=pads, offsets=offs, return_config=True)
+            assert np.array_equal(C, ref), (dtype, la, lb, lc, pads, offs, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_split_k_matches_oracle(oracle, dtype):
+    A, B = gi.make_problem(77, 192, 160, 1100, "uniform", dtype)
+    ref = ref_of(oracle, A, B, dtype)
+    for la, lb in LAYOUT_PAIRS:
+        for splits in (2, 5, 16):
+            C, cfg = run_gpu(dtype, A, B, la, lb, force="t64x64:s%d" % splits, return_config=True)
+            used = int(cfg.rsplit(" s", 1)[1])   # slices actually used (empty slices are dropped)
+            assert 1 < used <= splits, cfg
+            check(C, ref, A, B, dtype, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_degenerate_sizes(dtype):
+    import torch
+    import paper_2003_06324_amd as g
+    fn = g.gemm_f32 if dtype == "f32" else g.gemm_f16f32
+    npdt = np.float32 if dtype == "f32" else np.float16
+    # K == 0: C is the empty sum
+    C = run_gpu(dtype, np.zeros((5, 0), npdt), np.zeros((0, 9), npdt), 0, 0)
+    assert np.array_equal(C, np.zeros((5, 9), np.float32))
+    C = run_gpu(dtype, np.zeros((5, 0), npdt), np.zeros((0, 9), npdt), 1, 0, gi.COL_MAJOR, pads=(0, 0, 2))
+    assert np.array_equal(C, np.zeros((5, 9), np.float32))
+    # M == 0 or N == 0: nothing happens, no error
+    x = torch.ones(64, dtype=torch.float32, device="cuda")
+    assert fn(0, 4, 4, None, 0, 0, x, 0, 0, None, 0, 0) == 0
+    assert fn(4, 0, 4, x, 0, 0, None, 0, 0, None, 0, 0) == 0
+    # invalid arguments are rejected with a status, nothing is launched
+    assert fn(-1, 4, 4, x, 0, 0, x, 0, 0, x, 0, 0, check=False) == -1
+    assert fn(4, 4, 4, x, 0, 3, x, 0, 0, x, 0, 0, check=False) == -1   # lda < K
+    assert fn(4, 4, 4, x, 2, 0, x, 0, 0, x, 0, 0, check=False) == -1   # bad layout
+    assert fn(4, 4, 4, None, 0, 0, x, 0, 0, x, 0, 0, check=False) == -1  # null A
+    assert g.force_config("t1x1", check=False) == -3
+    torch.cuda.synchronize()
+
+
+def test_run_to_run_bit_identical():
+    # same launch twice: a race in the double buffer would show as differing bits
+    A, B = gi.make_problem(5, 640, 512, 1024, "normal", "f16")
+    for la, lb in LAYOUT_PAIRS:
+        first = run_gpu("f16", A, B, la, lb)
+        for _ in range(3):
+            assert np.array_equal(run_gpu("f16", A, B, la, lb), first)
+
+
+def test_inf_and_nan_only_where_the_inputs_put_them(oracle):
+    A, B = gi.make_problem(9, 130, 140, 70, "uniform", "f16")
+    A = A.copy()
+    A[3, 5] = np.inf
+    A[100, 69] = np.nan
+    ref = ref_of(oracle, A, B, "f16")
+    for la, lb in LAYOUT_PAIRS:
+        C = run_gpu("f16", A, B, la, lb)
+        assert np.array_equal(np.isnan(C), np.isnan(ref))
+        assert np.array_equal(np.isinf(C), np.isinf(ref))
+        ok = np.isfinite(ref)
+        assert np.max(np.abs(C[ok] - ref[ok])) <= 2e-4 * 70
