@@ -1,0 +1,176 @@
+"""Benchmark of the GEMM hot path on one MI355X.
+
+A step is one pass over the headline workload: the FP16-in / FP32-accumulate
+8192^3 product in all four operand layouts (NN, NT, TN, TT; N = row-major
+operand, T = column-major operand), i.e. four library calls.  Inputs are
+seeded synthetic matrices already resident in HBM.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3}   # MI355X dense MFMA peaks: 256 CU x 2.4 GHz x 4096 / 256 flop/clk/CU
+
+
+def device_operands(A, B, layout):
+    """Device buffers of logical torch matrices A (M x K), B (K x N) in the given layouts."""
+    import gemm_inputs as gi
+    la, lb = gi.LAYOUTS[layout]
+    dA = A.contiguous() if la == gi.ROW_MAJOR else A.t().contiguous()
+    dB = B.contiguous() if lb == gi.ROW_MAJOR else B.t().contiguous()
+    return dA, la, dB, lb
+
+
+def time_calls(fn, calls, steps, warmup):
+    """Run `calls` (list of argument tuples) per step; returns (wall seconds for `steps`
+    steps, per-call mean milliseconds from HIP events recorded on the launch stream)."""
+    import torch
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        for args in calls:
+            fn(*args, stream.cuda_stream)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        events[s][0].record(stream)
+        for i, args in enumerate(calls):
+            fn(*args, stream.cuda_stream)
+            events[s][i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_call = [sum(events[s][i].elapsed_time(events[s][i + 1]) for s in range(steps)) / steps
+                for i in range(len(calls))]
+    return wall, per_call
+
+
+def cpu_baseline(A_np, B_np, gpu_rows, target_seconds=15.0):
+    """Oracle timed on the host cores on the first rows of the NT case; also returns the
+    largest deviation of the GPU result on those rows (stated metric)."""
+    import numpy as np
+    import gemm_inputs as gi
+    from oracle import gemm_oracle
+    M, K = A_np.shape
+    N = B_np.shape[1]
+    Bt = gi.store(B_np, gi.COL_MAJOR)
+    gemm_oracle.build()
+
+    def run(rows):
+        t0 = time.perf_counter()
+        out, _ = gemm_oracle.gemm_f16_raw(rows, N, K, gi.store(A_np[:rows], gi.ROW_MAJOR), 0, 0, Bt, 1, 0)
+        return time.perf_counter() - t0, out
+
+    # time = fixed operand-widening cost + rows * per-row cost: two probes give both
+    t_a, _ = run(16)
+    t_b, _ = run(80)
+    per_row = max((t_b - t_a) / 64.0, 1e-9)
+    fixed = max(t_a - 16 * per_row, 0.0)
+    rows = int(max(64, min(M, 2048, (target_seconds - fixed) / per_row)))
+    secs, ref = run(rows)
+    ref = ref.reshape(rows, N)
+    got = gpu_rows(rows)
+    err = float(np.max(np.abs(got - ref)) / (K * float(np.abs(A_np).max()) * float(np.abs(B_np).max())))
+    return {"value": 2.0 * rows * N * K / secs / 1e12, "unit": "TFLOP/s", "cores": gemm_oracle.num_threads(),
+            "kind": "oracle", "seconds": round(secs, 2),
+            "sample": "first %d of %d rows of C of the NT case (%d x %d x %d), float64 triple loop" % (rows, M, rows, N, K)}, err
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--size", type=int, default=8192, help="M = N = K of the headline workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build is single-GPU (a GEMM tile needs no exchange; see DESIGN.md); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    import gemm_inputs as gi
+    import paper_2003_06324_amd as g
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    g.load_library()
+    torch.cuda.set_device(0)
+    S = args.size
+    # --- headline workload: FP16 in, FP32 accumulate, S^3, four layouts, N(0,1) entries, seed 3000
+    A_np, B_np = gi.make_problem(3000, S, S, S, "normal", "f16")
+    A = torch.from_numpy(A_np.view(np.int16)).cuda()
+    B = torch.from_numpy(B_np.view(np.int16)).cuda()
+    names = ["NN", "NT", "TN", "TT"]
+    keep, calls, outs = [], [], {}
+    for name in names:
+        dA, la, dB, lb = device_operands(A, B, name)
+        C = torch.empty(S * S, dtype=torch.float32, device="cuda")
+        keep.append((dA, dB, C))
+        outs[name] = C
+        calls.append((S, S, S, dA, la, 0, dB, lb, 0, C, gi.ROW_MAJOR, 0))
+    wall, per_call = time_calls(g.gemm_f16f32, calls, args.steps, args.warmup)
+    configs = {}
+    for name, c in zip(names, calls):
+        g.gemm_f16f32(*c, torch.cuda.current_stream().cuda_stream)
+        configs[name] = g.last_config()
+    torch.cuda.synchronize()
+    flop = 2.0 * S * S * S
+    ms_per_step = wall * 1e3 / args.steps
+    value = 4 * flop / (ms_per_step * 1e-3) / 1e12
+    per_layout = {n: {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1), "kernel": configs[n]}
+                  for n, ms in zip(names, per_call)}
+    # dominant kernel = the layout that takes the largest share of the step
+    dom = max(names, key=lambda n: per_layout[n]["ms"])
+    achieved = flop / per_layout[dom]["ms"] / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("f16_%d_%s" % (S, dom))
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_TFLOPS["f16"], 4), "traffic": traffic,
+                "kernel": per_layout[dom]["kernel"], "flop_per_launch": flop,
+                "avg_launch_ms": per_layout[dom]["ms"]}
+
+    # --- secondary workload (not part of the timed step): FP32 4096^3, A row-major, B column-major
+    A32_np, B32_np = gi.make_problem(2000, 4096, 4096, 4096, "uniform", "f32")
+    A32 = torch.from_numpy(A32_np).cuda()
+    B32 = torch.from_numpy(B32_np).cuda()
+    dA, la, dB, lb = device_operands(A32, B32, "NT")
+    C32 = torch.empty(4096 * 4096, dtype=torch.float32, device="cuda")
+    _, pc = time_calls(g.gemm_f32, [(4096, 4096, 4096, dA, la, 0, dB, lb, 0, C32, gi.ROW_MAJOR, 0)],
+                       max(5, args.steps // 2), 2)
+    f32_tflops = 2.0 * 4096 ** 3 / pc[0] / 1e9
+    fp32 = {"workload": "f32_4096x4096x4096_NT", "ms": round(pc[0], 4), "tflops": round(f32_tflops, 1),
+            "frac_of_peak": round(f32_tflops / PEAK_TFLOPS["f32"], 4), "peak": PEAK_TFLOPS["f32"],
+            "kernel": g.last_config()}
+
+    out = {
+        "metric": "GEMM TFLOP/s (FP16-in/FP32-acc, %d^3, mean over NN/NT/TN/TT) at 1 GPU" % S,
+        "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "f16f32_%dx%dx%d_NN+NT+TN+TT" % (S, S, S), "gemms_per_step": 4,
+                   "entries": "N(0,1) rounded to binary16, seed 3000", "C": "binary32 row-major"},
+        "pct_of_peak": round(100.0 * value / PEAK_TFLOPS["f16"], 2),
+        "per_layout": per_layout, "roofline": roofline, "fp32": fp32,
+    }
+    if not args.no_cpu_baseline:
+        def gpu_rows(rows):
+            return outs["NT"][: rows * S].cpu().numpy().reshape(rows, S)
+        base, err = cpu_baseline(A_np, B_np, gpu_rows)
+        out["cpu_baseline"] = base
+        out["parity_on_sample"] = {"max_err_over_K_maxA_maxB": err, "tolerance": 2e-4, "ok": bool(err <= 2e-4)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -234,7 +234,12 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     }
     const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n, 8)), (unsigned)splits);
     const launch_fn fn = f32 ? t.f32 : t.f16;
-    if (fn(akc, bkc, aligned, grid, stream, a) != hipSuccess) return GEMM_ERR_HIP;
+    const hipError_t launch_rc = fn(akc, bkc, aligned, grid, stream, a);
+    if (launch_rc != hipSuccess) {
+        if (getenv("GEMM_VERBOSE"))
+            fprintf(stderr, "gemm: launch of %s failed: %s\n", t.name, hipGetErrorString(launch_rc));
+        return GEMM_ERR_HIP;
+    }
     if (splits > 1) {
         const int64_t total = M * N;
         const int blocks = (int)(cdiv(total, 256) < 4096 ? cdiv(total, 256) : 4096);

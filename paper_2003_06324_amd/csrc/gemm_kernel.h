@@ -1,17 +1,27 @@
 // Tiled MFMA GEMM kernel for gfx950 (MI355X), wave64.
 //
 // One workgroup computes a BM x BN tile of C (the paper's block-level tile,
-// Section 3.2 "tile"), walks K in chunks of BK (its "split"), stages the
-// A and B chunks in LDS (its "load ... SH") with a double buffer, lets each
-// wave own a (BM/WM) x (BN/WN) sub-tile built from 32x32 MFMA blocks held in
-// accumulator registers (zero-filled first, stored last: its "epilog").
+// Section 3.2 "tile"), walks K in slabs of BK (its "split"), stages the A and B
+// slabs in LDS (its "load ... SH") through a ring of buffers that direct
+// global->LDS loads keep full, lets each wave own a (BM/WM) x (BN/WN) sub-tile
+// built from 32x32 MFMA blocks held in accumulator registers (zero-filled first,
+// stored last: its "epilog").
 //
-// LDS image of one operand chunk (the same bytes for f16 with BK = 64 and f32
-// with BK = 32: a K-row of the chunk is 128 bytes = eight 16-byte granules):
-//   K-contiguous operand (row-major A, column-major B): [tile row][128 B],
-//     granule g of row r is stored at granule position g ^ (r & 7);
+// A slab is KGS "k-groups"; a k-group is what one MFMA step consumes per lane
+// pair: 16 k for f16 (one v_mfma_f32_32x32x16_f16), 8 k for f32 (four
+// v_mfma_f32_32x32x2_f32), i.e. 32 bytes per tile row either way.  So both
+// types share one byte geometry: a slab row is 32*KGS bytes = 2*KGS granules of
+// 16 bytes.
+//
+// LDS image of one operand slab:
+//   K-contiguous operand (row-major A, column-major B): [tile row][32*KGS B],
+//     granule g of row r is stored at granule position g ^ swz_kc(r);
 //   M/N-contiguous operand (column-major A, row-major B): [k][R elements],
-//     granule g of k-row k is stored at position g ^ swz(k).
+//     granule g of k-row k is stored at position g ^ swz_mc(k).
+// The LDS serves 256 bytes per clock from 64 banks: a b128 read is processed
+// 16 lanes at a time and a b64 read 32 lanes at a time, so the swizzles are
+// chosen to spread every such lane group over all 64 banks.
+//
 // Both images are produced either by direct 16-byte global->LDS loads (each
 // wave fills 1 KiB of LDS per instruction, lane l writing bytes [16l, 16l+16),
 // so the swizzle is applied by choosing which global granule a lane fetches)
@@ -33,6 +43,14 @@ typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 #define GEMM_LDS(T) __attribute__((address_space(3))) T
 #define GEMM_GLB(T) __attribute__((address_space(1))) T
 
+#ifndef GEMM_KGS
+#define GEMM_KGS 2
+#endif
+constexpr int KGS = GEMM_KGS;    // k-groups per slab
+constexpr int GPR = 2 * KGS;      // granules per row of a K-contiguous image
+constexpr int RBK = 16 * GPR;     // bytes per row of a K-contiguous image
+constexpr int NSTAGE = 4;         // LDS ring depth of the direct-load pipeline
+
 struct KernelArgs {
     const void *A;       // M x K
     const void *B;       // K x N
@@ -41,34 +59,54 @@ struct KernelArgs {
     int64_t split_stride;  // elements between consecutive K-slices of the workspace
     int M, N, K;
     int tiles_m, tiles_n;
-    int kt_per_split;    // BK-chunks per K-slice (blockIdx.y selects the slice)
+    int kt_per_split;    // slabs per K-slice (blockIdx.y selects the slice)
 };
 
 template <typename T> struct Elem;
-template <> struct Elem<_Float16> { static constexpr int EPC = 8, BK = 64; };
-template <> struct Elem<float>    { static constexpr int EPC = 4, BK = 32; };
+template <> struct Elem<_Float16> { static constexpr int EPC = 8, KG = 16, BK = KG * KGS; };
+template <> struct Elem<float>    { static constexpr int EPC = 4, KG = 8, BK = KG * KGS; };
 
-// granule swizzle of an M/N-contiguous chunk, as a function of the k-row
-template <typename T> __device__ __forceinline__ int swz_mc(int k);
-template <> __device__ __forceinline__ int swz_mc<_Float16>(int k) { return (k & 3) << 1; }
-template <> __device__ __forceinline__ int swz_mc<float>(int k) { return ((k >> 2) & 1) << 3; }
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }        // vmcnt(n)
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }  // vmcnt(n) lgkmcnt(0)
+
+// Workgroup barrier that does not drain the vector-memory counter: direct loads for later
+// slabs stay in flight across it.  The "memory" clobber keeps the compiler from moving LDS
+// accesses over it; the waits that make the hand-over safe are issued by the caller.
+__device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_barrier" ::: "memory"); }
+
+// Granule swizzle of a K-contiguous image.  A b128 fragment read has 16 consecutive lanes
+// on 16 consecutive rows at one logical granule; 16/GPR rows share a 256-byte bank period,
+// so the row index above that picks the granule position.
+__device__ __forceinline__ int swz_kc(int r) { return (r / (16 / GPR)) & (GPR - 1); }
+
+// Granule swizzle of an M/N-contiguous image as a function of the k-row; CPR = granules
+// per k-row.  f16 (transposing b64 reads, 32 lanes cover 4 k-rows x 64 bytes): the four
+// rows go to four different 64-byte quarters of the bank space.  f32 (b32 reads, lanes
+// 0-31 on row k, lanes 32-63 on row k+4): the two rows go to different 128-byte halves.
+template <typename T, int CPR> __device__ __forceinline__ int swz_mc(int k)
+{
+    if (sizeof(T) == 2) return CPR >= 16 ? ((k & 3) << 2) : (((k >> 1) & 1) << 2);
+    return ((k >> 2) & 1) << 3;
+}
 
 // ---------------------------------------------------------------------------
-// Direct global->LDS loader for one operand chunk of R tile rows.
+// Direct global->LDS loader for one operand slab of R tile rows.
 // ---------------------------------------------------------------------------
 template <typename T, int R, int NW, bool KC>
 struct DirectLoader {
     static constexpr int EPC = Elem<T>::EPC, BK = Elem<T>::BK;
-    static constexpr int NLOADS = R / 8;  // 1 KiB wave-loads per chunk
+    static constexpr int NLOADS = R * RBK / 1024;  // 1 KiB wave-loads per slab
     static constexpr int PER_WAVE = NLOADS / NW;
     static_assert(NLOADS % NW == 0 && PER_WAVE >= 1, "tile too small for this wave count");
-    static constexpr int CPR = R / EPC;   // granules per k-row (M/N-contiguous image)
+    static constexpr int CPR = R / EPC;            // granules per k-row (M/N-contiguous image)
+    static constexpr int ROWS_PER_LOAD = 1024 / RBK;
 
     const T *src[PER_WAVE];
-    int64_t step;  // elements to advance per K chunk
+    int64_t step;  // elements to advance per slab
 
     // base: operand pointer; ld: leading dimension; row0: first tile row (m or n);
-    // rmax: matrix extent in that direction; k0: first k of the first chunk.
+    // rmax: matrix extent in that direction; k0: first k of the first slab.
     __device__ __forceinline__ void init(const T *base, int64_t ld, int row0, int rmax, int k0,
                                          int wave, int lane)
     {
@@ -76,15 +114,15 @@ struct DirectLoader {
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + i * NW;
             if (KC) {
-                const int r = 8 * j + (lane >> 3);
-                const int g = (lane & 7) ^ (lane >> 3);
+                const int r = ROWS_PER_LOAD * j + lane / GPR;
+                const int g = (lane % GPR) ^ swz_kc(r);
                 int row = row0 + r;
                 row = row < rmax ? row : rmax - 1;  // rows past the edge re-read the last one
                 src[i] = base + (int64_t)row * ld + k0 + g * EPC;
             } else {
                 const int q = 64 * j + lane;
                 const int kk = q / CPR;
-                const int g = (q % CPR) ^ swz_mc<T>(kk);
+                const int g = (q % CPR) ^ swz_mc<T, CPR>(kk);
                 int m = row0 + g * EPC;
                 m = m < rmax ? m : row0;  // granules past the edge re-read the first one
                 src[i] = base + (int64_t)(k0 + kk) * ld + m;
@@ -103,10 +141,12 @@ struct DirectLoader {
         }
     }
 
-    __device__ __forceinline__ void advance()
+    // move to the next slab if `more`, else stay (branch-free)
+    __device__ __forceinline__ void advance(bool more)
     {
+        const int64_t s = more ? step : 0;
 #pragma unroll
-        for (int i = 0; i < PER_WAVE; ++i) src[i] += step;
+        for (int i = 0; i < PER_WAVE; ++i) src[i] += s;
     }
 };
 
@@ -118,23 +158,24 @@ template <typename T, int R, int NT, bool KC>
 __device__ __forceinline__ void guarded_load(GEMM_LDS(char) *dst, const T *base, int64_t ld,
                                              int row0, int rmax, int k0, int kend, int tid)
 {
-    constexpr int EPC = Elem<T>::EPC, BK = Elem<T>::BK;
-    constexpr int NGRAN = R * 8;
+    constexpr int EPC = Elem<T>::EPC;
+    constexpr int NGRAN = R * GPR;
     constexpr int CPR = R / EPC;
-    static_assert(NGRAN % NT == 0, "granules must divide over the threads");
+    constexpr int ITERS = (NGRAN + NT - 1) / NT;
 #pragma unroll 2
-    for (int i = 0; i < NGRAN / NT; ++i) {
+    for (int i = 0; i < ITERS; ++i) {
         const int q = tid + i * NT;
+        if (NGRAN % NT != 0 && q >= NGRAN) break;
         T v[EPC];
         int off;
         if (KC) {
-            const int r = q >> 3, g = q & 7;
+            const int r = q / GPR, g = q % GPR;
             const int row = row0 + r, k = k0 + g * EPC;
             const T *p = base + (int64_t)row * ld + k;
             const int nvalid = row < rmax ? kend - k : 0;
 #pragma unroll
             for (int e = 0; e < EPC; ++e) v[e] = e < nvalid ? p[e] : (T)0;
-            off = r * 128 + ((g ^ (r & 7)) << 4);
+            off = r * RBK + ((g ^ swz_kc(r)) << 4);
         } else {
             const int kk = q / CPR, g = q % CPR;
             const int k = k0 + kk, m = row0 + g * EPC;
@@ -142,7 +183,7 @@ __device__ __forceinline__ void guarded_load(GEMM_LDS(char) *dst, const T *base,
             const int nvalid = k < kend ? rmax - m : 0;
 #pragma unroll
             for (int e = 0; e < EPC; ++e) v[e] = e < nvalid ? p[e] : (T)0;
-            off = kk * (CPR * 16) + ((g ^ swz_mc<T>(kk)) << 4);
+            off = kk * (CPR * 16) + ((g ^ swz_mc<T, CPR>(kk)) << 4);
         }
         uint4_t w;
         __builtin_memcpy(&w, v, 16);
@@ -151,8 +192,7 @@ __device__ __forceinline__ void guarded_load(GEMM_LDS(char) *dst, const T *base,
 }
 
 // ---------------------------------------------------------------------------
-// MFMA operand fetch from the LDS image.  One "k-group" is 16 k for f16 and
-// 8 k for f32; a chunk has 4 k-groups either way.
+// MFMA operand fetch from the LDS image, k-group kg of the slab.
 //   f16: returns the 8 halves lane l feeds to v_mfma_f32_32x32x16_f16 for
 //        block row/column (l & 31): k = 16*kg + 8*(l >> 5) + 0..7.
 //   f32: returns 4 floats; element t is what lane l feeds to the t-th
@@ -162,17 +202,13 @@ template <typename T> struct Frag;
 template <> struct Frag<_Float16> { typedef half8_t type; };
 template <> struct Frag<float> { typedef float4_t type; };
 
-// r0: first tile row of the 32-row block inside the chunk image
-template <typename T, int R, bool KC>
-__device__ __forceinline__ typename Frag<T>::type fetch(const GEMM_LDS(char) *img, int r0, int kg,
-                                                        int lane);
-
+// r0: first tile row of the 32-row block inside the slab image
 template <int R>
 __device__ __forceinline__ half8_t fetch_f16_kc(const GEMM_LDS(char) *img, int r0, int kg, int lane)
 {
     const int r = r0 + (lane & 31);
     const int g = 2 * kg + (lane >> 5);
-    return *(const GEMM_LDS(half8_t) *)(img + r * 128 + ((g ^ (r & 7)) << 4));
+    return *(const GEMM_LDS(half8_t) *)(img + r * RBK + ((g ^ swz_kc(r)) << 4));
 }
 
 template <int R>
@@ -190,7 +226,7 @@ __device__ __forceinline__ half8_t fetch_f16_mc(const GEMM_LDS(char) *img, int r
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         const int k = kq + 4 * t;
-        const int off = k * RB + ((((col >> 3) ^ swz_mc<_Float16>(k))) << 4) + ((col & 7) << 1);
+        const int off = k * RB + ((((col >> 3) ^ swz_mc<_Float16, R / 8>(k))) << 4) + ((col & 7) << 1);
         short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GEMM_LDS(short4_t) *)(img + off));
         half4_t h;
         __builtin_memcpy(&h, &v, 8);
@@ -207,7 +243,7 @@ __device__ __forceinline__ float4_t fetch_f32_kc(const GEMM_LDS(char) *img, int 
 {
     const int r = r0 + (lane & 31);
     const int g = 2 * kg + (lane >> 5);
-    return *(const GEMM_LDS(float4_t) *)(img + r * 128 + ((g ^ (r & 7)) << 4));
+    return *(const GEMM_LDS(float4_t) *)(img + r * RBK + ((g ^ swz_kc(r)) << 4));
 }
 
 template <int R>
@@ -219,7 +255,7 @@ __device__ __forceinline__ float4_t fetch_f32_mc(const GEMM_LDS(char) *img, int 
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int k = 8 * kg + 4 * (lane >> 5) + t;
-        const int off = k * RB + (((col >> 2) ^ swz_mc<float>(k)) << 4) + ((col & 3) << 2);
+        const int off = k * RB + (((col >> 2) ^ swz_mc<float, R / 4>(k)) << 4) + ((col & 3) << 2);
         out[t] = *(const GEMM_LDS(float) *)(img + off);
     }
     return out;
@@ -249,6 +285,34 @@ __device__ __forceinline__ void mma(float16_t &acc, const float4_t &a, const flo
     for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
 }
 
+// Scheduling hint for one k-group: the NDS LDS reads (operands of the next k-group) go
+// out one per MFMA at the start, so that the last of them has a long run of MFMAs to
+// land behind; the NVM direct loads, if any, are spread over the remaining MFMAs.
+template <int NDS, int NMMA, int NVM>
+__device__ __forceinline__ void interleave_hint()
+{
+    constexpr int DS_PER = (NDS + NMMA - 1) / NMMA;
+    constexpr int USED = (NDS + DS_PER - 1) / DS_PER;
+#pragma unroll
+    for (int i = 0; i < NDS; i += DS_PER) {
+        __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
+    }
+    if constexpr (NVM > 0) {
+        constexpr int REM = NMMA - USED;
+        if constexpr (REM > 0) {
+            constexpr int VM_PER = (NVM + REM - 1) / REM;
+#pragma unroll
+            for (int i = 0; i < NVM; i += VM_PER) {
+                __builtin_amdgcn_sched_group_barrier(0x020, VM_PER, 0);  // VMEM read
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x020, NVM, 0);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // The kernel.  grid.x = 8 * ceil(tiles/8) workgroups, grid.y = K-slices.
 // ---------------------------------------------------------------------------
@@ -259,10 +323,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     constexpr int BK = Elem<T>::BK;
     constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be built from 32x32 blocks");
-    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_BYTES = BM * RBK, B_BYTES = BN * RBK, STAGE = A_BYTES + B_BYTES;
+    constexpr int NBUF = ALIGNED ? NSTAGE : 1;
     typedef typename Frag<T>::type frag_t;
+    // LDS reads and MFMAs per k-group (for the interleave hints)
+    constexpr int RD_A = sizeof(T) == 2 ? (AKC ? 1 : 2) : (AKC ? 1 : 4);
+    constexpr int RD_B = sizeof(T) == 2 ? (BKC ? 1 : 2) : (BKC ? 1 : 4);
+    constexpr int NDS = FM * RD_A + FN * RD_B;
+    constexpr int NMMA = FM * FN * (sizeof(T) == 2 ? 1 : 4);
+    constexpr int NVM = (BM + BN) * RBK / 1024 / NW;  // direct loads per wave per slab
 
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) char smem[NBUF * STAGE];
     GEMM_LDS(char) *lds = (GEMM_LDS(char) *)smem;
 
     const int tid = threadIdx.x;
@@ -291,18 +362,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     const int kt0 = blockIdx.y * p.kt_per_split;
     int kt1 = kt0 + p.kt_per_split;
     kt1 = kt1 < KT ? kt1 : KT;
-    const int nkt = kt1 - kt0;
     const int kend = (kt1 * BK) < p.K ? (kt1 * BK) : p.K;
 
     const T *A = (const T *)p.A;
     const T *B = (const T *)p.B;
-
-    DirectLoader<T, BM, NW, AKC> la;
-    DirectLoader<T, BN, NW, BKC> lb;
-    if (ALIGNED) {
-        la.init(A, p.lda, m0, p.M, kt0 * BK, wave, lane);
-        lb.init(B, p.ldb, n0, p.N, kt0 * BK, wave, lane);
-    }
 
     float16_t acc[FM][FN];
 #pragma unroll
@@ -312,49 +375,101 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // stage chunk kt (absolute index) into buffer b
-    auto stage = [&](int kt, int b) {
-        GEMM_LDS(char) *dA = lds + b * STAGE;
-        GEMM_LDS(char) *dB = dA + A_BYTES;
-        const int k0 = kt * BK;
-        if (ALIGNED && k0 + BK <= kend) {
-            la.issue(dA, wave);
-            lb.issue(dB, wave);
-            la.advance();
-            lb.advance();
-        } else {
-            guarded_load<T, BM, NT, AKC>(dA, A, p.lda, m0, p.M, k0, kend, tid);
-            guarded_load<T, BN, NT, BKC>(dB, B, p.ldb, n0, p.N, k0, kend, tid);
-        }
+    auto read_frags = [&](frag_t(&fa)[FM], frag_t(&fb)[FN], const GEMM_LDS(char) * iA, int kg) {
+        const GEMM_LDS(char) *iB = iA + A_BYTES;
+        // in the order the MFMAs (row-major over the blocks) first need them
+        fa[0] = Fetch<T, BM, AKC>::get(iA, wm * TM, kg, lane);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[j] = Fetch<T, BN, BKC>::get(iB, wn * TN + j * 32, kg, lane);
+#pragma unroll
+        for (int i = 1; i < FM; ++i) fa[i] = Fetch<T, BM, AKC>::get(iA, wm * TM + i * 32, kg, lane);
+    };
+    auto mma_all = [&](const frag_t(&fa)[FM], const frag_t(&fb)[FN]) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) mma(acc[i][j], fa[i], fb[j]);
     };
 
-    if (nkt > 0) {
-        stage(kt0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-        __syncthreads();
-    }
+    int k_done = kt0 * BK;  // first k not yet accumulated
+    if (ALIGNED) {
+        // Full slabs: direct global->LDS loads into a ring of NSTAGE buffers, operand
+        // registers double-buffered per k-group.  While slab s is multiplied, slabs s+1 ..
+        // s+NSTAGE-1 are landed or in flight (the prologue fills all NSTAGE buffers).  One barrier per slab, placed before its last
+        // k-group: by then every wave holds that k-group's operands in registers, so the
+        // buffer of slab s can be refilled with slab s+NSTAGE while the last MFMAs of slab s
+        // run and the first operands of slab s+1 are fetched.  Past the end of K the refill
+        // re-fetches the last slab (never read), which keeps the loop body branch-free and
+        // the number of outstanding loads constant for the counted waits.
+        const int n = (kend - k_done) / BK;
+        if (n > 0) {
+            DirectLoader<T, BM, NW, AKC> la;
+            DirectLoader<T, BN, NW, BKC> lb;
+            la.init(A, p.lda, m0, p.M, k_done, wave, lane);
+            lb.init(B, p.ldb, n0, p.N, k_done, wave, lane);
+#pragma unroll
+            for (int s = 0; s < NSTAGE; ++s) {  // the loaders always point at the next slab to fetch
+                la.issue(lds + s * STAGE, wave);
+                lb.issue(lds + s * STAGE + A_BYTES, wave);
+                la.advance(s + 1 < n);
+                lb.advance(s + 1 < n);
+            }
+            // slab 0 has landed once only the NSTAGE-1 younger slabs are outstanding
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NVM));
+            barrier_keep_loads();
 
-    for (int it = 0; it < nkt; ++it) {
-        const int cur = it & 1;
-        if (it + 1 < nkt) stage(kt0 + it + 1, cur ^ 1);
-
-        const GEMM_LDS(char) *iA = lds + cur * STAGE;
-        const GEMM_LDS(char) *iB = iA + A_BYTES;
+            frag_t fa[2][FM], fb[2][FN];
+            read_frags(fa[0], fb[0], lds, 0);
+            int stage = 0;  // ring position of slab s
+            for (int s = 0; s < n - 1; ++s) {
+                const GEMM_LDS(char) *cur = lds + stage * STAGE;
+                stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+                const GEMM_LDS(char) *nxt = lds + stage * STAGE;
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg) {
-            frag_t a[FM], b[FN];
+                for (int kg = 0; kg < KGS - 1; ++kg) {
+                    read_frags(fa[(kg + 1) & 1], fb[(kg + 1) & 1], cur, kg + 1);
+                    mma_all(fa[kg & 1], fb[kg & 1]);
+                    interleave_hint<NDS, NMMA, 0>();
+                }
+                // issued so far: slabs 0 .. s+NSTAGE-1.  Slab s+1 has landed (own loads) once only
+                // the NSTAGE-2 younger ones are outstanding; own reads of slab s are done.
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSTAGE - 2) * NVM));
+                barrier_keep_loads();
+                la.issue((GEMM_LDS(char) *)cur, wave);
+                lb.issue((GEMM_LDS(char) *)cur + A_BYTES, wave);
+                la.advance(s + NSTAGE + 1 < n);
+                lb.advance(s + NSTAGE + 1 < n);
+                read_frags(fa[KGS & 1], fb[KGS & 1], nxt, 0);
+                mma_all(fa[(KGS - 1) & 1], fb[(KGS - 1) & 1]);
+                interleave_hint<NDS, NMMA, NVM>();
+            }
+            {
+                const GEMM_LDS(char) *cur = lds + stage * STAGE;
 #pragma unroll
-            for (int i = 0; i < FM; ++i) a[i] = Fetch<T, BM, AKC>::get(iA, wm * TM + i * 32, kg, lane);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) b[j] = Fetch<T, BN, BKC>::get(iB, wn * TN + j * 32, kg, lane);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j) mma(acc[i][j], a[i], b[j]);
+                for (int kg = 0; kg < KGS - 1; ++kg) {
+                    read_frags(fa[(kg + 1) & 1], fb[(kg + 1) & 1], cur, kg + 1);
+                    mma_all(fa[kg & 1], fb[kg & 1]);
+                    interleave_hint<NDS, NMMA, 0>();
+                }
+                mma_all(fa[(KGS - 1) & 1], fb[(KGS - 1) & 1]);
+            }
+            k_done += n * BK;
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant refills
         }
-        // the next chunk has landed (own loads) and everyone is done reading this one
-        __builtin_amdgcn_s_waitcnt(0x0070);
+    }
+    // Remaining slabs (a ragged tail, or everything when operands are unaligned):
+    // guarded loads through registers, one buffer, two barriers per slab.
+    for (; k_done < kend; k_done += BK) {
         __syncthreads();
+        guarded_load<T, BM, NT, AKC>(lds, A, p.lda, m0, p.M, k_done, kend, tid);
+        guarded_load<T, BN, NT, BKC>(lds + A_BYTES, B, p.ldb, n0, p.N, k_done, kend, tid);
+        __syncthreads();
+#pragma unroll
+        for (int kg = 0; kg < KGS; ++kg) {
+            frag_t fa[FM], fb[FN];
+            read_frags(fa, fb, lds, kg);
+            mma_all(fa, fb);
+        }
     }
 
     // epilogue: accumulator register r of lane l holds

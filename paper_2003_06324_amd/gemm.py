@@ -36,6 +36,13 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         from . import build as _build
         _build.build()
+    # One HIP runtime per process: PyTorch ships its own libamdhip64 under the same soname
+    # as the system one.  Importing torch first makes this library bind to the runtime
+    # that owns the caller's tensors and streams, whatever the import order.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
     i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
     sig = [i64, i64, i64, p, i32, i64, p, i32, i64, p, i32, i64, p]

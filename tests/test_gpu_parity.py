@@ -55,8 +55,10 @@ def test_integer_bit_exact_every_tile(oracle, dtype, tile):
 def test_k_loop_lengths(oracle, dtype):
     # every K-loop trip count from a lone partial chunk to three chunks and a tail,
     # on aligned and unaligned leading dimensions (double-buffer hand-over)
-    bk = 64 if dtype == "f16" else 32
-    ks = [1, 2, 7, 8, bk - 1, bk, bk + 1, bk + 8, 2 * bk, 2 * bk + 8, 3 * bk, 3 * bk + 1, 3 * bk + 16]
+    # bk = K-slab of the kernels; the direct-load ring is 4 slabs deep
+    bk = 32 if dtype == "f16" else 16
+    ks = [1, 2, 7, 8, bk - 1, bk, bk + 1, bk + 8, 2 * bk, 3 * bk + 8, 4 * bk, 4 * bk + 1, 5 * bk,
+          6 * bk + 16, 9 * bk, 13 * bk + 8]
     for K in ks:
         A, B = gi.make_problem(900 + K, 136, 72, K, "int", dtype)
         ref = ref_of(oracle, A, B, dtype).astype(np.float32)
