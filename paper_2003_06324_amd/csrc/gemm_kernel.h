@@ -2,7 +2,7 @@
 //
 // One workgroup computes a BM x BN tile of C (the paper's block-level tile,
 // Section 3.2 "tile"), walks K in slabs of BK (its "split"), stages the A and B
-// slabs in LDS (its "load ... SH") through a ring of buffers that direct
+// slabs in LDS (its "load ... SH") through a ring of operand slots that direct
 // global->LDS loads keep full, lets each wave own a (BM/WM) x (BN/WN) sub-tile
 // built from 32x32 MFMA blocks held in accumulator registers (zero-filled first,
 // stored last: its "epilog").
@@ -30,6 +30,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace gemm_gfx950 {
 
@@ -39,17 +40,19 @@ typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef int int2_t __attribute__((ext_vector_type(2)));
+typedef int int4_t __attribute__((ext_vector_type(4)));
 
 #define GEMM_LDS(T) __attribute__((address_space(3))) T
 #define GEMM_GLB(T) __attribute__((address_space(1))) T
 
 #ifndef GEMM_KGS
-#define GEMM_KGS 2
+#define GEMM_KGS 4
 #endif
 constexpr int KGS = GEMM_KGS;    // k-groups per slab
 constexpr int GPR = 2 * KGS;      // granules per row of a K-contiguous image
 constexpr int RBK = 16 * GPR;     // bytes per row of a K-contiguous image
-constexpr int NSTAGE = 4;         // LDS ring depth of the direct-load pipeline
+constexpr int NSLOT = 5;          // operand slots in the LDS ring of the direct-load pipeline
 
 struct KernelArgs {
     const void *A;       // M x K
@@ -68,6 +71,7 @@ template <> struct Elem<float>    { static constexpr int EPC = 4, KG = 8, BK = K
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }        // vmcnt(n)
+constexpr int waitcnt_lgkm0() { return 0xC07F; }                                        // lgkmcnt(0)
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }  // vmcnt(n) lgkmcnt(0)
 
 // Workgroup barrier that does not drain the vector-memory counter: direct loads for later
@@ -131,14 +135,24 @@ struct DirectLoader {
         step = KC ? (int64_t)BK : (int64_t)BK * ld;
     }
 
-    __device__ __forceinline__ void issue(GEMM_LDS(char) *dst, int wave)
+    // issue this wave's loads number [i0, i1) of the current slab into the slot at dst
+    __device__ __forceinline__ void issue(GEMM_LDS(char) *dst, int wave, int i0 = 0, int i1 = PER_WAVE)
     {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
+            if (i < i0 || i >= i1) continue;
             const int j = wave + i * NW;
             __builtin_amdgcn_global_load_lds((const GEMM_GLB(void) *)src[i],
                                              (GEMM_LDS(void) *)(dst + j * 1024), 16, 0, 0);
         }
+    }
+
+    // issue this wave's load number i (compile-time constant after unrolling)
+    __device__ __forceinline__ void issue1(GEMM_LDS(char) *dst, int wave, int i)
+    {
+        const int j = wave + i * NW;
+        __builtin_amdgcn_global_load_lds((const GEMM_GLB(void) *)src[i],
+                                         (GEMM_LDS(void) *)(dst + j * 1024), 16, 0, 0);
     }
 
     // move to the next slab if `more`, else stay (branch-free)
@@ -211,8 +225,20 @@ __device__ __forceinline__ half8_t fetch_f16_kc(const GEMM_LDS(char) *img, int r
     return *(const GEMM_LDS(half8_t) *)(img + r * RBK + ((g ^ swz_kc(r)) << 4));
 }
 
-template <int R>
-__device__ __forceinline__ half8_t fetch_f16_mc(const GEMM_LDS(char) *img, int r0, int kg, int lane)
+// Transposing LDS read, issued as inline assembly: the compiler cannot tell that this read
+// does not touch the slots the in-flight direct loads are filling and would drain the
+// vector-memory counter in front of the builtin form.  The compiler does not see the read
+// as outstanding either, so every caller waits (lgkmcnt) before the result is used.
+template <int IMM>
+__device__ __forceinline__ int2_t lds_read_tr16_b64(const GEMM_LDS(char) *p)
+{
+    int2_t v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(p), "n"(IMM) : "memory");
+    return v;
+}
+
+template <int R, int KG_>
+__device__ __forceinline__ half8_t fetch_f16_mc_kg(const GEMM_LDS(char) *img, int r0, int lane)
 {
     // ds_read_b64_tr_b16: within each group of 16 lanes the 16 x 4 halves the
     // lanes point at are read as a [4][16] array (lane s supplies row s/4,
@@ -221,21 +247,26 @@ __device__ __forceinline__ half8_t fetch_f16_mc(const GEMM_LDS(char) *img, int r
     constexpr int RB = R * 2;
     const int s = lane & 15;
     const int col = r0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
-    const int kq = 16 * kg + 8 * (lane >> 5) + (s >> 2);
+    const int kl = 8 * (lane >> 5) + (s >> 2);  // lane part of k; the rest (16*kg + 4*t) is a multiple of 4
+    const GEMM_LDS(char) *p = img + kl * RB + ((((col >> 3) ^ swz_mc<_Float16, R / 8>(kl))) << 4) + ((col & 7) << 1);
+    const int2_t lo = lds_read_tr16_b64<(16 * KG_) * RB>(p);
+    const int2_t hi = lds_read_tr16_b64<(16 * KG_ + 4) * RB>(p);
+    // the two 64-bit results are the low and high half of the 128-bit MFMA operand
+    const int4_t whole = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
     half8_t out;
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int k = kq + 4 * t;
-        const int off = k * RB + ((((col >> 3) ^ swz_mc<_Float16, R / 8>(k))) << 4) + ((col & 7) << 1);
-        short4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GEMM_LDS(short4_t) *)(img + off));
-        half4_t h;
-        __builtin_memcpy(&h, &v, 8);
-        out[4 * t + 0] = h[0];
-        out[4 * t + 1] = h[1];
-        out[4 * t + 2] = h[2];
-        out[4 * t + 3] = h[3];
-    }
+    __builtin_memcpy(&out, &whole, 16);
     return out;
+}
+
+template <int R>
+__device__ __forceinline__ half8_t fetch_f16_mc(const GEMM_LDS(char) *img, int r0, int kg, int lane)
+{
+    switch (kg) {  // kg is a compile-time constant at every call site
+    case 0: return fetch_f16_mc_kg<R, 0>(img, r0, lane);
+    case 1: return fetch_f16_mc_kg<R, 1>(img, r0, lane);
+    case 2: return fetch_f16_mc_kg<R, 2>(img, r0, lane);
+    default: return fetch_f16_mc_kg<R, 3>(img, r0, lane);
+    }
 }
 
 template <int R>
@@ -285,34 +316,6 @@ __device__ __forceinline__ void mma(float16_t &acc, const float4_t &a, const flo
     for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
 }
 
-// Scheduling hint for one k-group: the NDS LDS reads (operands of the next k-group) go
-// out one per MFMA at the start, so that the last of them has a long run of MFMAs to
-// land behind; the NVM direct loads, if any, are spread over the remaining MFMAs.
-template <int NDS, int NMMA, int NVM>
-__device__ __forceinline__ void interleave_hint()
-{
-    constexpr int DS_PER = (NDS + NMMA - 1) / NMMA;
-    constexpr int USED = (NDS + DS_PER - 1) / DS_PER;
-#pragma unroll
-    for (int i = 0; i < NDS; i += DS_PER) {
-        __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);  // DS read
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
-    }
-    if constexpr (NVM > 0) {
-        constexpr int REM = NMMA - USED;
-        if constexpr (REM > 0) {
-            constexpr int VM_PER = (NVM + REM - 1) / REM;
-#pragma unroll
-            for (int i = 0; i < NVM; i += VM_PER) {
-                __builtin_amdgcn_sched_group_barrier(0x020, VM_PER, 0);  // VMEM read
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            }
-        } else {
-            __builtin_amdgcn_sched_group_barrier(0x020, NVM, 0);
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------
 // The kernel.  grid.x = 8 * ceil(tiles/8) workgroups, grid.y = K-slices.
 // ---------------------------------------------------------------------------
@@ -323,17 +326,22 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     constexpr int BK = Elem<T>::BK;
     constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be built from 32x32 blocks");
-    constexpr int A_BYTES = BM * RBK, B_BYTES = BN * RBK, STAGE = A_BYTES + B_BYTES;
-    constexpr int NBUF = ALIGNED ? NSTAGE : 1;
+    constexpr int A_BYTES = BM * RBK, B_BYTES = BN * RBK;
+    constexpr int SLOT = A_BYTES > B_BYTES ? A_BYTES : B_BYTES;  // one operand slab
+    constexpr int NBUF = ALIGNED ? NSLOT : 2;
     typedef typename Frag<T>::type frag_t;
     // LDS reads and MFMAs per k-group (for the interleave hints)
     constexpr int RD_A = sizeof(T) == 2 ? (AKC ? 1 : 2) : (AKC ? 1 : 4);
     constexpr int RD_B = sizeof(T) == 2 ? (BKC ? 1 : 2) : (BKC ? 1 : 4);
     constexpr int NDS = FM * RD_A + FN * RD_B;
     constexpr int NMMA = FM * FN * (sizeof(T) == 2 ? 1 : 4);
-    constexpr int NVM = (BM + BN) * RBK / 1024 / NW;  // direct loads per wave per slab
+    // f16 M/N-contiguous operands are fetched by inline-assembly reads the compiler does not track
+    constexpr bool ASM_READS = sizeof(T) == 2 && (!AKC || !BKC);
+    constexpr int NVA = A_BYTES / 1024 / NW;  // direct loads per wave per A slab
+    constexpr int NVB = B_BYTES / 1024 / NW;
+    static_assert(KGS == 4, "the pipeline below is written for four k-groups per slab");
 
-    __shared__ __attribute__((aligned(1024))) char smem[NBUF * STAGE];
+    __shared__ __attribute__((aligned(1024))) char smem[NBUF * SLOT];
     GEMM_LDS(char) *lds = (GEMM_LDS(char) *)smem;
 
     const int tid = threadIdx.x;
@@ -375,31 +383,62 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    auto read_frags = [&](frag_t(&fa)[FM], frag_t(&fb)[FN], const GEMM_LDS(char) * iA, int kg) {
-        const GEMM_LDS(char) *iB = iA + A_BYTES;
-        // in the order the MFMAs (row-major over the blocks) first need them
-        fa[0] = Fetch<T, BM, AKC>::get(iA, wm * TM, kg, lane);
+    // One k-group of work in a fixed instruction order (the compiler may not move anything
+    // across the fences): MFMA block m = i*FN + j is followed by the m-th operand fetch of
+    // the NEXT k-group (order a0, b0..b(FN-1), a1..a(FM-1): what the first MFMAs of that
+    // k-group need comes first) and by its share of the NL direct loads `load(q)`, so LDS
+    // reads and global loads trickle out between MFMAs instead of in bursts that would
+    // fill the address queues and stall this wave's MFMA stream.
+    auto kgroup = [&](const frag_t(&ca)[FM], const frag_t(&cb)[FN], frag_t(&na)[FM], frag_t(&nb)[FN],
+                      const GEMM_LDS(char) * iA, const GEMM_LDS(char) * iB, int kg_next, bool fetch,
+                      auto load, auto nl_tag) {
+        constexpr int NL = decltype(nl_tag)::value;
+        constexpr int NB = FM * FN, NF = FM + FN;
+        if (ASM_READS) {
+            // operands fetched in the previous k-group; fenced, or MFMAs could be moved above the wait
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
-        for (int j = 0; j < FN; ++j) fb[j] = Fetch<T, BN, BKC>::get(iB, wn * TN + j * 32, kg, lane);
+        for (int m = 0; m < NB; ++m) {
+            mma(acc[m / FN][m % FN], ca[m / FN], cb[m % FN]);
+            if (fetch) {
 #pragma unroll
-        for (int i = 1; i < FM; ++i) fa[i] = Fetch<T, BM, AKC>::get(iA, wm * TM + i * 32, kg, lane);
+                for (int f = 0; f < NF; ++f) {
+                    // fetch f is issued with block m = f, leftovers with the last block
+                    if ((f < NB ? f : NB - 1) != m) continue;
+                    if (f == 0) na[0] = Fetch<T, BM, AKC>::get(iA, wm * TM, kg_next, lane);
+                    else if (f <= FN) nb[f - 1] = Fetch<T, BN, BKC>::get(iB, wn * TN + (f - 1) * 32, kg_next, lane);
+                    else na[f - FN] = Fetch<T, BM, AKC>::get(iA, wm * TM + (f - FN) * 32, kg_next, lane);
+                }
+            }
+            if constexpr (NL > 0) {
+#pragma unroll
+                for (int q = 0; q < NL; ++q)
+                    if (q * NB / NL == m) load(q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
-    auto mma_all = [&](const frag_t(&fa)[FM], const frag_t(&fb)[FN]) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j) mma(acc[i][j], fa[i], fb[j]);
-    };
+    auto no_load = [](int) {};
+    typedef std::integral_constant<int, 0> L0;
 
     int k_done = kt0 * BK;  // first k not yet accumulated
     if (ALIGNED) {
-        // Full slabs: direct global->LDS loads into a ring of NSTAGE buffers, operand
-        // registers double-buffered per k-group.  While slab s is multiplied, slabs s+1 ..
-        // s+NSTAGE-1 are landed or in flight (the prologue fills all NSTAGE buffers).  One barrier per slab, placed before its last
-        // k-group: by then every wave holds that k-group's operands in registers, so the
-        // buffer of slab s can be refilled with slab s+NSTAGE while the last MFMAs of slab s
-        // run and the first operands of slab s+1 are fetched.  Past the end of K the refill
-        // re-fetches the last slab (never read), which keeps the loop body branch-free and
+        // Full slabs: direct global->LDS loads into a ring of NSLOT = 5 operand slots.
+        // Operand slabs are fetched in the order A(0) B(0) A(1) B(1) ..., slab number h going
+        // to slot h % 5, so tile t has A in slot 2t % 5 and B in the next one, and one slot
+        // is always spare.  Per tile t (four k-groups, operand registers double-buffered):
+        //   k-groups 0,1: MFMAs; fetch operands of the next k-group; issue A(t+2) into
+        //                 the spare slot, half of its loads per k-group;
+        //   k-group 2:    MFMAs; fetch operands of k-group 3;
+        //   counted wait: everything but A(t+2) has landed, i.e. tile t+1 is complete;
+        //   barrier:      every wave holds k-group 3 in registers, tile t's slots are free;
+        //   k-group 3:    MFMAs; issue B(t+2) into A(t)'s slot; fetch k-group 0 of tile t+1.
+        // So loads are in flight all the time (32..96 KiB of the 160 KiB LDS), A slabs have
+        // two tiles of MFMA time to land and B slabs one.  Past the end of K the loaders
+        // re-fetch the last slab (never read), which keeps the loop body branch-free and
         // the number of outstanding loads constant for the counted waits.
         const int n = (kend - k_done) / BK;
         if (n > 0) {
@@ -407,51 +446,54 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             DirectLoader<T, BN, NW, BKC> lb;
             la.init(A, p.lda, m0, p.M, k_done, wave, lane);
             lb.init(B, p.ldb, n0, p.N, k_done, wave, lane);
-#pragma unroll
-            for (int s = 0; s < NSTAGE; ++s) {  // the loaders always point at the next slab to fetch
-                la.issue(lds + s * STAGE, wave);
-                lb.issue(lds + s * STAGE + A_BYTES, wave);
-                la.advance(s + 1 < n);
-                lb.advance(s + 1 < n);
-            }
-            // slab 0 has landed once only the NSTAGE-1 younger slabs are outstanding
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NVM));
+            // A(0) B(0) A(1) B(1); the loaders then point at tile 2 (or the last tile)
+            la.issue(lds + 0 * SLOT, wave);
+            la.advance(1 < n);
+            lb.issue(lds + 1 * SLOT, wave);
+            lb.advance(1 < n);
+            la.issue(lds + 2 * SLOT, wave);
+            la.advance(2 < n);
+            lb.issue(lds + 3 * SLOT, wave);
+            lb.advance(2 < n);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NVA + NVB));  // tile 0 landed
             barrier_keep_loads();
 
             frag_t fa[2][FM], fb[2][FN];
-            read_frags(fa[0], fb[0], lds, 0);
-            int stage = 0;  // ring position of slab s
-            for (int s = 0; s < n - 1; ++s) {
-                const GEMM_LDS(char) *cur = lds + stage * STAGE;
-                stage = stage + 1 == NSTAGE ? 0 : stage + 1;
-                const GEMM_LDS(char) *nxt = lds + stage * STAGE;
+            fa[0][0] = Fetch<T, BM, AKC>::get(lds, wm * TM, 0, lane);
 #pragma unroll
-                for (int kg = 0; kg < KGS - 1; ++kg) {
-                    read_frags(fa[(kg + 1) & 1], fb[(kg + 1) & 1], cur, kg + 1);
-                    mma_all(fa[kg & 1], fb[kg & 1]);
-                    interleave_hint<NDS, NMMA, 0>();
-                }
-                // issued so far: slabs 0 .. s+NSTAGE-1.  Slab s+1 has landed (own loads) once only
-                // the NSTAGE-2 younger ones are outstanding; own reads of slab s are done.
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSTAGE - 2) * NVM));
+            for (int j = 0; j < FN; ++j) fb[0][j] = Fetch<T, BN, BKC>::get(lds + SLOT, wn * TN + j * 32, 0, lane);
+#pragma unroll
+            for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(lds, wm * TM + i * 32, 0, lane);
+            int sa = 0;  // slot of A(t); B(t) is in the next one
+            auto slot = [&](int d) -> GEMM_LDS(char) * {
+                int x = sa + d;
+                x = x >= NSLOT ? x - NSLOT : x;
+                return lds + x * SLOT;
+            };
+            for (int t = 0; t < n - 1; ++t) {
+                const GEMM_LDS(char) *cA = slot(0), *cB = slot(1);
+                const GEMM_LDS(char) *nA = slot(2), *nB = slot(3);
+                GEMM_LDS(char) *spare = slot(4);
+                auto load_a_lo = [&](int q) { la.issue1(spare, wave, q); };
+                auto load_a_hi = [&](int q) { la.issue1(spare, wave, NVA / 2 + q); };
+                auto load_b = [&](int q) { lb.issue1((GEMM_LDS(char) *)cA, wave, q); };
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, load_a_lo, std::integral_constant<int, NVA / 2>());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, load_a_hi, std::integral_constant<int, NVA - NVA / 2>());
+                la.advance(t + 3 < n);
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
+                // tile t+1 landed (all but the youngest NVA loads), own reads of tile t done
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVA));
                 barrier_keep_loads();
-                la.issue((GEMM_LDS(char) *)cur, wave);
-                lb.issue((GEMM_LDS(char) *)cur + A_BYTES, wave);
-                la.advance(s + NSTAGE + 1 < n);
-                lb.advance(s + NSTAGE + 1 < n);
-                read_frags(fa[KGS & 1], fb[KGS & 1], nxt, 0);
-                mma_all(fa[(KGS - 1) & 1], fb[(KGS - 1) & 1]);
-                interleave_hint<NDS, NMMA, NVM>();
+                kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_b, std::integral_constant<int, NVB>());
+                lb.advance(t + 3 < n);
+                sa = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
             }
             {
-                const GEMM_LDS(char) *cur = lds + stage * STAGE;
-#pragma unroll
-                for (int kg = 0; kg < KGS - 1; ++kg) {
-                    read_frags(fa[(kg + 1) & 1], fb[(kg + 1) & 1], cur, kg + 1);
-                    mma_all(fa[kg & 1], fb[kg & 1]);
-                    interleave_hint<NDS, NMMA, 0>();
-                }
-                mma_all(fa[(KGS - 1) & 1], fb[(KGS - 1) & 1]);
+                const GEMM_LDS(char) *cA = slot(0), *cB = slot(1);
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 0, false, no_load, L0());
             }
             k_done += n * BK;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant refills
@@ -462,13 +504,24 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     for (; k_done < kend; k_done += BK) {
         __syncthreads();
         guarded_load<T, BM, NT, AKC>(lds, A, p.lda, m0, p.M, k_done, kend, tid);
-        guarded_load<T, BN, NT, BKC>(lds + A_BYTES, B, p.ldb, n0, p.N, k_done, kend, tid);
+        guarded_load<T, BN, NT, BKC>(lds + SLOT, B, p.ldb, n0, p.N, k_done, kend, tid);
         __syncthreads();
 #pragma unroll
         for (int kg = 0; kg < KGS; ++kg) {
             frag_t fa[FM], fb[FN];
-            read_frags(fa, fb, lds, kg);
-            mma_all(fa, fb);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) fa[i] = Fetch<T, BM, AKC>::get(lds, wm * TM + i * 32, kg, lane);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[j] = Fetch<T, BN, BKC>::get(lds + SLOT, wn * TN + j * 32, kg, lane);
+            if (ASM_READS) {
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) mma(acc[i][j], fa[i], fb[j]);
         }
     }
 
