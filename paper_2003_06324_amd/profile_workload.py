@@ -1,0 +1,61 @@
+"""Small driver for rocprofv3 runs: launches one GEMM configuration a few times and,
+optionally, a plain device-to-device copy of known size whose FETCH_SIZE / WRITE_SIZE
+readings calibrate the HBM-traffic counters.
+
+    python3 -m paper_2003_06324_amd.profile_workload --dtype f16 --size 8192 --layout NT --iters 5 --copy-mib 1024
+"""
+import argparse
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--dtype", choices=["f16", "f32"], default="f16")
+    ap.add_argument("--size", type=int, nargs="+", default=[8192], help="M N K, or one value for a cube")
+    ap.add_argument("--layout", choices=["NN", "NT", "TN", "TT"], default="NT")
+    ap.add_argument("--dist", choices=["normal", "uniform", "zeros"], default="normal")
+    ap.add_argument("--iters", type=int, default=5)
+    ap.add_argument("--copy-mib", type=int, default=0, help="also run a copy kernel of this many MiB")
+    ap.add_argument("--force", default=None, help="tile configuration override, e.g. t256x256")
+    args = ap.parse_args()
+
+    import torch
+    import gemm_inputs as gi
+    import paper_2003_06324_amd as g
+
+    M, N, K = (args.size * 3)[:3] if len(args.size) == 1 else args.size
+    tdt = torch.float16 if args.dtype == "f16" else torch.float32
+    gen = torch.Generator(device="cuda").manual_seed(0)
+
+    def draw(n):
+        if args.dist == "zeros":
+            return torch.zeros(n, dtype=tdt, device="cuda")
+        x = torch.empty(n, dtype=torch.float32, device="cuda")
+        x.normal_(generator=gen) if args.dist == "normal" else x.uniform_(-1, 1, generator=gen)
+        return x.to(tdt)
+
+    A, B = draw(M * K), draw(K * N)
+    C = torch.empty(M * N, dtype=torch.float32, device="cuda")
+    la, lb = gi.LAYOUTS[args.layout]
+    fn = g.gemm_f16f32 if args.dtype == "f16" else g.gemm_f32
+    stream = torch.cuda.current_stream().cuda_stream
+    g.force_config(args.force)
+    for _ in range(args.iters):
+        fn(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
+    torch.cuda.synchronize()
+    print("gemm:", g.last_config(), "x", args.iters)
+    if args.copy_mib:
+        n = args.copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print("copy: %d MiB read + %d MiB written, x3" % (args.copy_mib, args.copy_mib))
+
+
+if __name__ == "__main__":
+    main()
