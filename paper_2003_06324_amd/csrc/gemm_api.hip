@@ -15,9 +15,11 @@ using namespace gemm_gfx950;
 
 namespace gemm_gfx950 {
 GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(_Float16, 128, 128, 2, 2)
 GEMM_DECLARE_TILE(_Float16, 64, 64, 2, 2)
 GEMM_DECLARE_TILE(float, 256, 256, 2, 2)
+GEMM_DECLARE_TILE(float, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(float, 128, 128, 2, 2)
 GEMM_DECLARE_TILE(float, 64, 64, 2, 2)
 }  // namespace gemm_gfx950
@@ -63,6 +65,7 @@ const TileConfig kTiles[] = {
     {"t256x256", 256, 256, 1, 1.00, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
     {"t128x128", 128, 128, 2, 0.70, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
     {"t64x64", 64, 64, 4, 0.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
+    {"t256x256w8", 256, 256, 1, 0.90, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -196,6 +199,9 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && (lda % EPC == 0) && (ldb % EPC == 0);
     if (!akc && M % EPC != 0) aligned = false;
     if (!bkc && N % EPC != 0) aligned = false;
+
+    // the direct loaders address a tile with 32-bit byte offsets from its origin
+    if (256 * lda * (int64_t)sizeof(T) >= (1LL << 31) || 256 * ldb * (int64_t)sizeof(T) >= (1LL << 31)) aligned = false;
 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;

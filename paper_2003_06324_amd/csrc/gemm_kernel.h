@@ -106,33 +106,40 @@ struct DirectLoader {
     static constexpr int CPR = R / EPC;            // granules per k-row (M/N-contiguous image)
     static constexpr int ROWS_PER_LOAD = 1024 / RBK;
 
-    const T *src[PER_WAVE];
-    int64_t step;  // elements to advance per slab
+    // Address of a lane's granule = wave-uniform base (scalar registers, advanced per slab)
+    // + a 32-bit per-lane byte offset that never changes.  The loads are buffer loads
+    // (scalar resource descriptor + vector offset), so the K loop spends no vector
+    // instructions on pointers.
+    const char *base;
+    uint32_t off[PER_WAVE];
+    int64_t step;  // bytes to advance per slab
 
-    // base: operand pointer; ld: leading dimension; row0: first tile row (m or n);
+    // origin: operand pointer; ld: leading dimension; row0: first tile row (m or n);
     // rmax: matrix extent in that direction; k0: first k of the first slab.
-    __device__ __forceinline__ void init(const T *base, int64_t ld, int row0, int rmax, int k0,
+    // The host guarantees that R * ld * sizeof(T) is below 2^31.
+    __device__ __forceinline__ void init(const T *origin, int64_t ld, int row0, int rmax, int k0,
                                          int wave, int lane)
     {
+        base = (const char *)(KC ? origin + (int64_t)row0 * ld + k0 : origin + (int64_t)k0 * ld + row0);
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + i * NW;
             if (KC) {
                 const int r = ROWS_PER_LOAD * j + lane / GPR;
                 const int g = (lane % GPR) ^ swz_kc(r);
-                int row = row0 + r;
-                row = row < rmax ? row : rmax - 1;  // rows past the edge re-read the last one
-                src[i] = base + (int64_t)row * ld + k0 + g * EPC;
+                int row = r;
+                row = row0 + row < rmax ? row : rmax - 1 - row0;  // rows past the edge re-read the last one
+                off[i] = (uint32_t)(((int64_t)row * ld + g * EPC) * (int64_t)sizeof(T));
             } else {
                 const int q = 64 * j + lane;
                 const int kk = q / CPR;
                 const int g = (q % CPR) ^ swz_mc<T, CPR>(kk);
-                int m = row0 + g * EPC;
-                m = m < rmax ? m : row0;  // granules past the edge re-read the first one
-                src[i] = base + (int64_t)(k0 + kk) * ld + m;
+                int m = g * EPC;
+                m = row0 + m < rmax ? m : 0;  // granules past the edge re-read the first one
+                off[i] = (uint32_t)(((int64_t)kk * ld + m) * (int64_t)sizeof(T));
             }
         }
-        step = KC ? (int64_t)BK : (int64_t)BK * ld;
+        step = (KC ? (int64_t)BK : (int64_t)BK * ld) * (int64_t)sizeof(T);
     }
 
     // issue this wave's loads number [i0, i1) of the current slab into the slot at dst
@@ -141,27 +148,25 @@ struct DirectLoader {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             if (i < i0 || i >= i1) continue;
-            const int j = wave + i * NW;
-            __builtin_amdgcn_global_load_lds((const GEMM_GLB(void) *)src[i],
-                                             (GEMM_LDS(void) *)(dst + j * 1024), 16, 0, 0);
+            issue1(dst, wave, i);
         }
     }
 
     // issue this wave's load number i (compile-time constant after unrolling)
     __device__ __forceinline__ void issue1(GEMM_LDS(char) *dst, int wave, int i)
     {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc must not see the buffer builtins
         const int j = wave + i * NW;
-        __builtin_amdgcn_global_load_lds((const GEMM_GLB(void) *)src[i],
-                                         (GEMM_LDS(void) *)(dst + j * 1024), 16, 0, 0);
+        // raw buffer descriptor: no stride, 2 GiB window from base (every offset used is below
+        // it and inside the operand by construction), 32-bit data format word
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0x7fffffff, 0x00020000);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (GEMM_LDS(void) *)(dst + j * 1024), 16, off[i], 0, 0, 0);
+#endif
     }
 
     // move to the next slab if `more`, else stay (branch-free)
-    __device__ __forceinline__ void advance(bool more)
-    {
-        const int64_t s = more ? step : 0;
-#pragma unroll
-        for (int i = 0; i < PER_WAVE; ++i) src[i] += s;
-    }
+    __device__ __forceinline__ void advance(bool more) { base += more ? step : 0; }
 };
 
 // ---------------------------------------------------------------------------
