@@ -171,42 +171,84 @@ struct DirectLoader {
 
 // ---------------------------------------------------------------------------
 // Guarded loader through registers: any alignment, zero-fills outside the
-// matrix and outside [.., kend).  Writes the same LDS image as DirectLoader.
+// matrix and outside [.., kend).  Produces the same LDS image as DirectLoader,
+// in two steps so that the global loads of the next slab can be in flight
+// while the current one is multiplied: guarded_fetch (global -> registers) and
+// staged_store (registers -> LDS).  A granule that lies fully inside the
+// matrix is fetched with one 16-byte load (element-aligned only: the compiler
+// picks the widest access the target allows), a ragged one element by element.
 // ---------------------------------------------------------------------------
+template <typename T, int R, int NT>
+struct Staged {
+    static constexpr int NGRAN = R * GPR;
+    static constexpr int ITERS = (NGRAN + NT - 1) / NT;
+    uint4_t v[ITERS];
+};
+
+// position of granule q of a slab: global pointer, number of valid elements, LDS byte offset
+template <typename T, int R, bool KC>
+__device__ __forceinline__ void granule_of(int q, const T *base, int64_t ld, int row0, int rmax, int k0,
+                                           int kend, const T *&p, int &nvalid, int &off)
+{
+    constexpr int EPC = Elem<T>::EPC;
+    constexpr int CPR = R / EPC;
+    if (KC) {
+        const int r = q / GPR, g = q % GPR;
+        const int row = row0 + r, k = k0 + g * EPC;
+        p = base + (int64_t)row * ld + k;
+        nvalid = row < rmax ? kend - k : 0;
+        off = r * RBK + ((g ^ swz_kc(r)) << 4);
+    } else {
+        const int kk = q / CPR, g = q % CPR;
+        const int k = k0 + kk, m = row0 + g * EPC;
+        p = base + (int64_t)k * ld + m;
+        nvalid = k < kend ? rmax - m : 0;
+        off = kk * (CPR * 16) + ((g ^ swz_mc<T, CPR>(kk)) << 4);
+    }
+}
+
+// global -> registers: whole granules only (ragged ones are left zero, see staged_store)
 template <typename T, int R, int NT, bool KC>
-__device__ __forceinline__ void guarded_load(GEMM_LDS(char) *dst, const T *base, int64_t ld,
-                                             int row0, int rmax, int k0, int kend, int tid)
+__device__ __forceinline__ void guarded_fetch(Staged<T, R, NT> &st, const T *base, int64_t ld,
+                                              int row0, int rmax, int k0, int kend, int tid)
 {
     constexpr int EPC = Elem<T>::EPC;
     constexpr int NGRAN = R * GPR;
-    constexpr int CPR = R / EPC;
-    constexpr int ITERS = (NGRAN + NT - 1) / NT;
-#pragma unroll 2
-    for (int i = 0; i < ITERS; ++i) {
+#pragma unroll
+    for (int i = 0; i < Staged<T, R, NT>::ITERS; ++i) {
+        const int q = tid + i * NT;
+        const T *p;
+        int nvalid, off;
+        granule_of<T, R, KC>(q, base, ld, row0, rmax, k0, kend, p, nvalid, off);
+        if (NGRAN % NT != 0 && q >= NGRAN) nvalid = 0;
+        uint4_t w = {0u, 0u, 0u, 0u};
+        if (nvalid >= EPC) __builtin_memcpy(&w, p, 16);
+        st.v[i] = w;
+    }
+}
+
+// registers -> LDS; the few granules that straddle the matrix edge or the end of K are
+// completed here, element by element, straight from global memory
+template <typename T, int R, int NT, bool KC>
+__device__ __forceinline__ void staged_store(GEMM_LDS(char) *dst, const Staged<T, R, NT> &st,
+                                             const T *base, int64_t ld, int row0, int rmax, int k0,
+                                             int kend, int tid)
+{
+    constexpr int EPC = Elem<T>::EPC;
+    constexpr int NGRAN = R * GPR;
+#pragma unroll
+    for (int i = 0; i < Staged<T, R, NT>::ITERS; ++i) {
         const int q = tid + i * NT;
         if (NGRAN % NT != 0 && q >= NGRAN) break;
-        T v[EPC];
-        int off;
-        if (KC) {
-            const int r = q / GPR, g = q % GPR;
-            const int row = row0 + r, k = k0 + g * EPC;
-            const T *p = base + (int64_t)row * ld + k;
-            const int nvalid = row < rmax ? kend - k : 0;
-#pragma unroll
-            for (int e = 0; e < EPC; ++e) v[e] = e < nvalid ? p[e] : (T)0;
-            off = r * RBK + ((g ^ swz_kc(r)) << 4);
-        } else {
-            const int kk = q / CPR, g = q % CPR;
-            const int k = k0 + kk, m = row0 + g * EPC;
-            const T *p = base + (int64_t)k * ld + m;
-            const int nvalid = k < kend ? rmax - m : 0;
-#pragma unroll
-            for (int e = 0; e < EPC; ++e) v[e] = e < nvalid ? p[e] : (T)0;
-            off = kk * (CPR * 16) + ((g ^ swz_mc<T, CPR>(kk)) << 4);
+        const T *p;
+        int nvalid, off;
+        granule_of<T, R, KC>(q, base, ld, row0, rmax, k0, kend, p, nvalid, off);
+        *(GEMM_LDS(uint4_t) *)(dst + off) = st.v[i];
+        if (nvalid > 0 && nvalid < EPC) {
+            GEMM_LDS(T) *d = (GEMM_LDS(T) *)(dst + off);
+#pragma unroll 1
+            for (int x = 0; x < nvalid; ++x) d[x] = p[x];
         }
-        uint4_t w;
-        __builtin_memcpy(&w, v, 16);
-        *(GEMM_LDS(uint4_t) *)(dst + off) = w;
     }
 }
 
@@ -387,6 +429,16 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    // Keeps the accumulators in the accumulation registers at this point (an empty asm with an
+    // "a" constraint): without it the register allocator parks part of them in ordinary
+    // vector registers across the guarded loop and spills the staging registers instead.
+    auto pin_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+    };
+    pin_acc();
 
     // One k-group of work in a fixed instruction order (the compiler may not move anything
     // across the fences): MFMA block m = i*FN + j is followed by the m-th operand fetch of
@@ -504,29 +556,45 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant refills
         }
     }
-    // Remaining slabs (a ragged tail, or everything when operands are unaligned):
-    // guarded loads through registers, one buffer, two barriers per slab.
-    for (; k_done < kend; k_done += BK) {
+    // Remaining slabs (a ragged tail, or everything when operands are unaligned): guarded
+    // loads through registers into one LDS buffer; the loads of slab s+1 are issued before
+    // slab s is multiplied and written to LDS after it.
+    if (k_done < kend) {
+        Staged<T, BM, NT> sa_;
+        Staged<T, BN, NT> sb_;
+        __syncthreads();  // LDS is free (direct-load pipeline drained, all reads done)
+        guarded_fetch<T, BM, NT, AKC>(sa_, A, p.lda, m0, p.M, k_done, kend, tid);
+        guarded_fetch<T, BN, NT, BKC>(sb_, B, p.ldb, n0, p.N, k_done, kend, tid);
+        staged_store<T, BM, NT, AKC>(lds, sa_, A, p.lda, m0, p.M, k_done, kend, tid);
+        staged_store<T, BN, NT, BKC>(lds + SLOT, sb_, B, p.ldb, n0, p.N, k_done, kend, tid);
         __syncthreads();
-        guarded_load<T, BM, NT, AKC>(lds, A, p.lda, m0, p.M, k_done, kend, tid);
-        guarded_load<T, BN, NT, BKC>(lds + SLOT, B, p.ldb, n0, p.N, k_done, kend, tid);
-        __syncthreads();
-#pragma unroll
-        for (int kg = 0; kg < KGS; ++kg) {
-            frag_t fa[FM], fb[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) fa[i] = Fetch<T, BM, AKC>::get(lds, wm * TM + i * 32, kg, lane);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) fb[j] = Fetch<T, BN, BKC>::get(lds + SLOT, wn * TN + j * 32, kg, lane);
-            if (ASM_READS) {
-                __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-                __builtin_amdgcn_sched_barrier(0);
+        for (; k_done < kend; k_done += BK) {
+            const bool more = k_done + BK < kend;
+            pin_acc();
+            if (more) {
+                guarded_fetch<T, BM, NT, AKC>(sa_, A, p.lda, m0, p.M, k_done + BK, kend, tid);
+                guarded_fetch<T, BN, NT, BKC>(sb_, B, p.ldb, n0, p.N, k_done + BK, kend, tid);
             }
+            {
+                // same fixed-order k-groups as the last tile of the direct-load pipeline
+                frag_t fa[2][FM], fb[2][FN];
+                const GEMM_LDS(char) *cA = lds, *cB = lds + SLOT;
+                fa[0][0] = Fetch<T, BM, AKC>::get(cA, wm * TM, 0, lane);
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+                for (int j = 0; j < FN; ++j) fb[0][j] = Fetch<T, BN, BKC>::get(cB, wn * TN + j * 32, 0, lane);
 #pragma unroll
-                for (int j = 0; j < FN; ++j) mma(acc[i][j], fa[i], fb[j]);
+                for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(cA, wm * TM + i * 32, 0, lane);
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 0, false, no_load, L0());
+            }
+            if (more) {
+                __syncthreads();  // everyone is done reading this slab
+                staged_store<T, BM, NT, AKC>(lds, sa_, A, p.lda, m0, p.M, k_done + BK, kend, tid);
+                staged_store<T, BN, NT, BKC>(lds + SLOT, sb_, B, p.ldb, n0, p.N, k_done + BK, kend, tid);
+                __syncthreads();
+            }
         }
     }
 
