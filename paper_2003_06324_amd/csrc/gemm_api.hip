@@ -56,16 +56,20 @@ constexpr int NUM_CU = 256;
 struct TileConfig {
     const char *name;
     int BM, BN;
-    int wg_per_cu;     // resident workgroups per CU (LDS-limited)
-    double rate;       // relative MFMA efficiency of the steady-state loop
+    int wg_per_cu;              // resident workgroups per CU (LDS-limited)
+    double f16_alone, f16_full; // microseconds per 64-k slab: one workgroup on a CU / CU fully occupied
+    double f32_alone, f32_full; // same per 32-k f32 slab
+    double general;             // slowdown of the guarded (unaligned) path
     launch_fn f16, f32;
 };
 
+// Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
+// under sustained MFMA load; these are not clock-peak figures).
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.00, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
-    {"t128x128", 128, 128, 2, 0.70, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
-    {"t64x64", 64, 64, 4, 0.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
-    {"t256x256w8", 256, 256, 1, 0.90, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>},
+    {"t256x256", 256, 256, 1, 2.0, 2.0, 7.9, 7.9, 1.85, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
+    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.8, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
+    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.55, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
+    {"t256x256w8", 256, 256, 1, 2.02, 2.02, 7.95, 7.95, 1.33, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -79,39 +83,53 @@ thread_local char t_last_config[128] = "none";
 
 int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Rough cost of running (tile, splits) in units of "one CU doing one
-// 256x256x(BK) step at full rate"; only the ordering between candidates matters.
-double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t KT, int splits, bool f32)
+// Estimated run time in microseconds of (tile, splits) on this shape.  Three floors: the
+// MFMA work as scheduled on 256 CUs (rounds of resident workgroups, slab time depending on
+// how many workgroups share a CU), HBM traffic for the unique bytes (limited by how many
+// bytes the resident workgroups keep in flight), and L2->CU traffic for all the bytes the
+// workgroups pull; plus launch/fill/drain and, with K slices, the reduce pass.
+double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64_t KT, int splits, bool f32,
+                     bool aligned)
 {
     const int64_t tiles = cdiv(M, t.BM) * cdiv(N, t.BN);
-    const int64_t kt_slice = cdiv(KT, splits);
+    const int64_t per = cdiv(KT, splits);
+    const int64_t S = cdiv(KT, per);
+    const int64_t W = tiles * S;
     const double slots = (double)NUM_CU * t.wg_per_cu;
-    const double rounds = (double)cdiv(tiles * splits, (int64_t)slots);
-    // a workgroup's time: its MFMA work at the tile's rate, slowed down by sharing the CU
-    const double step = (double)t.BM * t.BN / (256.0 * 256.0) / t.rate;
-    const double prologue = f32 ? 1.0 : 6.0;  // fill latency + epilogue, in 256x256 steps
-    double cost = rounds * t.wg_per_cu * (step * (double)kt_slice + prologue * step + 1.0);
-    if (splits > 1) {
-        // workspace write + read + final write against ~4 TB/s, plus a second launch,
-        // converted to steps (one f16 step ~0.85 us, one f32 step ~6.8 us at full rate)
-        const double bytes = (double)M * N * 4.0 * (2.0 * splits + 1.0);
-        const double step_us = f32 ? 6.8 : 0.85;
-        cost += (bytes / 4.0e6 + 4.0) / step_us;
+    const double rounds = (double)cdiv(W, (int64_t)slots);
+    const int64_t share = cdiv(W, NUM_CU) < t.wg_per_cu ? cdiv(W, NUM_CU) : t.wg_per_cu;
+    const double alone = f32 ? t.f32_alone : t.f16_alone, full = f32 ? t.f32_full : t.f16_full;
+    double slab = alone + (t.wg_per_cu > 1 ? (full - alone) * (double)(share - 1) / (t.wg_per_cu - 1) : 0.0);
+    if (!aligned) {
+        // the guarded path exposes one global-load round trip (~2.2 us) per slab, hidden only by
+        // the other workgroups on the CU
+        slab *= t.general;
+        if (slab < 2.2 / (double)share) slab = 2.2 / (double)share;
     }
+    const double t_mfma = rounds * ((double)per * slab + 1.0);
+    const double esz = f32 ? 4.0 : 2.0;
+    const double unique = ((double)M * K + (double)K * N) * esz + (double)M * N * 4.0;
+    const double resident = (double)W < slots ? (double)W : slots;
+    double hbm_rate = resident * 1.5 * (t.BM + t.BN) * 128.0 / 2.0;  // bytes/us the workgroups keep in flight
+    if (hbm_rate > 4.5e6) hbm_rate = 4.5e6;
+    const double t_hbm = unique / hbm_rate;
+    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / 14.0e6;
+    double cost = 5.0 + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
+    if (S > 1) cost += 4.0 + (double)M * N * 4.0 * (double)(S + 1) / 3.0e6;
     return cost;
 }
 
-void choose(int64_t M, int64_t N, int64_t KT, bool f32, int &tile, int &splits)
+void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, bool aligned, int &tile, int &splits)
 {
     double best = 1e300;
     tile = g_forced_tile >= 0 ? g_forced_tile : 0;
     splits = 1;
     for (int t = 0; t < kNumTiles; ++t) {
         if (g_forced_tile >= 0 && t != g_forced_tile) continue;
-        for (int s = 1; s <= 64; s *= 2) {
+        for (int s = 1; s <= 32; s *= 2) {
             const int cand = g_forced_splits > 0 ? g_forced_splits : s;
             if (cand > 1 && cand > KT) break;
-            const double c = estimate_cost(kTiles[t], M, N, KT, cand, f32);
+            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, aligned);
             if (c < best) { best = c; tile = t; splits = cand; }
             if (g_forced_splits > 0) break;
         }
@@ -207,7 +225,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, KT, f32, tile, splits);
+        choose(M, N, K, KT, f32, aligned, tile, splits);
     }
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
