@@ -84,8 +84,8 @@ def cpu_baseline(A_np, B_np, gpu_rows, target_seconds=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -147,7 +147,7 @@ def main():
     dA, la, dB, lb = device_operands(A32, B32, "NT")
     C32 = torch.empty(4096 * 4096, dtype=torch.float32, device="cuda")
     _, pc = time_calls(g.gemm_f32, [(4096, 4096, 4096, dA, la, 0, dB, lb, 0, C32, gi.ROW_MAJOR, 0)],
-                       max(5, args.steps // 2), 2)
+                       max(5, args.steps), max(2, args.warmup))
     f32_tflops = 2.0 * 4096 ** 3 / pc[0] / 1e9
     fp32 = {"workload": "f32_4096x4096x4096_NT", "ms": round(pc[0], 4), "tflops": round(f32_tflops, 1),
             "frac_of_peak": round(f32_tflops / PEAK_TFLOPS["f32"], 4), "peak": PEAK_TFLOPS["f32"],

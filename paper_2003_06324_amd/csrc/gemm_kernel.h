@@ -37,6 +37,7 @@ namespace gemm_gfx950 {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef __fp16 fp16x4_t __attribute__((__vector_size__(4 * sizeof(__fp16))));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
@@ -71,7 +72,6 @@ template <> struct Elem<float>    { static constexpr int EPC = 4, KG = 8, BK = K
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }        // vmcnt(n)
-constexpr int waitcnt_lgkm0() { return 0xC07F; }                                        // lgkmcnt(0)
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }  // vmcnt(n) lgkmcnt(0)
 
 // Workgroup barrier that does not drain the vector-memory counter: direct loads for later
@@ -155,14 +155,24 @@ struct DirectLoader {
     // issue this wave's load number i (compile-time constant after unrolling)
     __device__ __forceinline__ void issue1(GEMM_LDS(char) *dst, int wave, int i)
     {
-#if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc must not see the buffer builtins
+        // Issued as inline assembly on purpose.  If the compiler sees an LDS-DMA load it makes
+        // every later LDS read it cannot prove disjoint wait for vmcnt(0), which would drain
+        // the load pipeline at each operand fetch; the kernel orders loads and reads itself
+        // (counted vmcnt waits + barrier).  The compiler's own vmcnt waits stay safe: loads
+        // complete in order, so extra outstanding loads only make a counted wait stricter.
         const int j = wave + i * NW;
-        // raw buffer descriptor: no stride, 2 GiB window from base (every offset used is below
-        // it and inside the operand by construction), 32-bit data format word
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0x7fffffff, 0x00020000);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (GEMM_LDS(void) *)(dst + j * 1024), 16, off[i], 0, 0, 0);
-#endif
+        // raw buffer descriptor: base, no stride, 2 GiB window (every offset used is below it
+        // and inside the operand by construction), 32-bit data format word
+        int4_t rsrc;
+        rsrc[0] = (int)(uint32_t)(uintptr_t)base;
+        rsrc[1] = (int)(uint32_t)((uintptr_t)base >> 32) & 0xffff;
+        rsrc[2] = 0x7fffffff;
+        rsrc[3] = 0x00020000;
+        const uint32_t lds_addr = (uint32_t)(uintptr_t)(dst + j * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     :
+                     : "s"(lds_addr), "v"(off[i]), "s"(rsrc)
+                     : "memory", "m0");
     }
 
     // move to the next slab if `more`, else stay (branch-free)
@@ -272,18 +282,6 @@ __device__ __forceinline__ half8_t fetch_f16_kc(const GEMM_LDS(char) *img, int r
     return *(const GEMM_LDS(half8_t) *)(img + r * RBK + ((g ^ swz_kc(r)) << 4));
 }
 
-// Transposing LDS read, issued as inline assembly: the compiler cannot tell that this read
-// does not touch the slots the in-flight direct loads are filling and would drain the
-// vector-memory counter in front of the builtin form.  The compiler does not see the read
-// as outstanding either, so every caller waits (lgkmcnt) before the result is used.
-template <int IMM>
-__device__ __forceinline__ int2_t lds_read_tr16_b64(const GEMM_LDS(char) *p)
-{
-    int2_t v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(p), "n"(IMM) : "memory");
-    return v;
-}
-
 template <int R, int KG_>
 __device__ __forceinline__ half8_t fetch_f16_mc_kg(const GEMM_LDS(char) *img, int r0, int lane)
 {
@@ -296,12 +294,12 @@ __device__ __forceinline__ half8_t fetch_f16_mc_kg(const GEMM_LDS(char) *img, in
     const int col = r0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
     const int kl = 8 * (lane >> 5) + (s >> 2);  // lane part of k; the rest (16*kg + 4*t) is a multiple of 4
     const GEMM_LDS(char) *p = img + kl * RB + ((((col >> 3) ^ swz_mc<_Float16, R / 8>(kl))) << 4) + ((col & 7) << 1);
-    const int2_t lo = lds_read_tr16_b64<(16 * KG_) * RB>(p);
-    const int2_t hi = lds_read_tr16_b64<(16 * KG_ + 4) * RB>(p);
+    const half4_t lo = __builtin_bit_cast(
+        half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4f16((GEMM_LDS(fp16x4_t) *)(p + (16 * KG_) * RB)));
+    const half4_t hi = __builtin_bit_cast(
+        half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4f16((GEMM_LDS(fp16x4_t) *)(p + (16 * KG_ + 4) * RB)));
     // the two 64-bit results are the low and high half of the 128-bit MFMA operand
-    const int4_t whole = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-    half8_t out;
-    __builtin_memcpy(&out, &whole, 16);
+    const half8_t out = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return out;
 }
 
@@ -382,8 +380,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     constexpr int RD_B = sizeof(T) == 2 ? (BKC ? 1 : 2) : (BKC ? 1 : 4);
     constexpr int NDS = FM * RD_A + FN * RD_B;
     constexpr int NMMA = FM * FN * (sizeof(T) == 2 ? 1 : 4);
-    // f16 M/N-contiguous operands are fetched by inline-assembly reads the compiler does not track
-    constexpr bool ASM_READS = sizeof(T) == 2 && (!AKC || !BKC);
     constexpr int NVA = A_BYTES / 1024 / NW;  // direct loads per wave per A slab
     constexpr int NVB = B_BYTES / 1024 / NW;
     static_assert(KGS == 4, "the pipeline below is written for four k-groups per slab");
@@ -451,12 +447,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                       auto load, auto nl_tag) {
         constexpr int NL = decltype(nl_tag)::value;
         constexpr int NB = FM * FN, NF = FM + FN;
-        if (ASM_READS) {
-            // operands fetched in the previous k-group; fenced, or MFMAs could be moved above the wait
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-            __builtin_amdgcn_sched_barrier(0);
-        }
 #pragma unroll
         for (int m = 0; m < NB; ++m) {
             mma(acc[m / FN][m % FN], ca[m / FN], cb[m % FN]);

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 LAYS = (gi.ROW_MAJOR, gi.COL_MAJOR)
 LAYOUT_PAIRS = list(itertools.product(LAYS, repeat=2))
-TILES = ["t256x256", "t128x128", "t64x64"]
+TILES = ["t256x256", "t256x256w8", "t128x128", "t64x64"]
 
 # several tiles of every configuration plus ragged tails in every dimension
 SHAPES = [(256, 256, 256), (300, 200, 100), (129, 257, 65), (513, 383, 130), (64, 72, 520),
@@ -63,7 +63,7 @@ def test_k_loop_lengths(oracle, dtype):
         A, B = gi.make_problem(900 + K, 136, 72, K, "int", dtype)
         ref = ref_of(oracle, A, B, dtype).astype(np.float32)
         for la, lb in LAYOUT_PAIRS:
-            for tile in ("t128x128", "t64x64"):
+            for tile in ("t128x128", "t64x64", "t256x256w8"):
                 C = run_gpu(dtype, A, B, la, lb, force=tile)
                 assert np.array_equal(C, ref), (dtype, K, la, lb, tile)
 
