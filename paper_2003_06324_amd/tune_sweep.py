@@ -1,0 +1,78 @@
+"""Exhaustive sweep of tile configurations and K-slice counts on a list of shapes, the way the
+paper tunes its block tile per input size (Section 5.3: powers of two, small sizes up to 1024
+and large sizes 1024..4096).  Prints, per shape, the automatic choice, the best forced
+configuration and the ratio between the two; the cost model in csrc/gemm_api.hip was
+calibrated on this output.
+
+    python3 -m paper_2003_06324_amd.tune_sweep            # default shape list
+    python3 -m paper_2003_06324_amd.tune_sweep f16 1536 1024 2048 NT
+"""
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+DEFAULT_SHAPES = [
+    # benchmark configurations
+    ("f32", 256, 256, 256, "NN"), ("f32", 4096, 4096, 4096, "NT"), ("f16", 8192, 8192, 8192, "NT"),
+    ("f16", 1000, 1500, 2000, "NN"), ("f16", 4097, 3073, 1025, "NN"), ("f16", 8192, 128, 8192, "TN"),
+    ("f16", 128, 8192, 8192, "TN"), ("f16", 1024, 1024, 65536, "TN"),
+    # the paper's own sizes: its headline 1536x1024x2048 NT, small (<= 1024) and large (1024..4096)
+    ("f16", 1536, 1024, 2048, "NT"), ("f16", 256, 256, 256, "NT"), ("f16", 512, 512, 512, "NT"),
+    ("f16", 1024, 1024, 1024, "NT"), ("f16", 2048, 2048, 2048, "NT"), ("f16", 4096, 4096, 4096, "NT"),
+    ("f16", 1024, 4096, 2048, "NN"), ("f16", 4096, 1024, 1024, "TT"),
+    ("f32", 1024, 1024, 1024, "NT"), ("f32", 2048, 2048, 2048, "NT"),
+]
+
+
+def main():
+    import torch
+    import gemm_inputs as gi
+    import paper_2003_06324_amd as g
+
+    shapes = DEFAULT_SHAPES
+    if len(sys.argv) == 6:
+        shapes = [(sys.argv[1], int(sys.argv[2]), int(sys.argv[3]), int(sys.argv[4]), sys.argv[5])]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, iters):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3  # microseconds
+
+    worst = 1.0
+    for dt, M, N, K, lay in shapes:
+        tdt = torch.float16 if dt == "f16" else torch.float32
+        A = torch.randn(M * K, device="cuda", dtype=tdt)
+        B = torch.randn(K * N, device="cuda", dtype=tdt)
+        C = torch.empty(M * N, device="cuda", dtype=torch.float32)
+        la, lb = gi.LAYOUTS[lay]
+        call = g.gemm_f16f32 if dt == "f16" else g.gemm_f32
+        fn = lambda: call(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
+        g.force_config(None)
+        t_auto = timed(fn, 20)
+        auto_cfg = g.last_config()
+        results = []
+        for tile in g.config_names():
+            for s in (1, 2, 4, 8, 16, 32):
+                g.force_config("%s:s%d" % (tile, s))
+                results.append((timed(fn, 10), tile, s))
+        g.force_config(None)
+        results.sort()
+        best = results[0]
+        worst = max(worst, t_auto / best[0])
+        print("%s %dx%dx%d %s: auto %.1f us [%s] | best %.1f us %s:s%d | auto/best %.2f | %.1f TFLOP/s" % (
+            dt, M, N, K, lay, t_auto, auto_cfg, best[0], best[1], best[2], t_auto / best[0],
+            2.0 * M * N * K / t_auto / 1e6), flush=True)
+    print("worst auto/best ratio: %.2f" % worst)
+
+
+if __name__ == "__main__":
+    main()

@@ -109,3 +109,23 @@ def test_f16_deep_k(oracle):
     _, Ai, Bi, _, _ = gi.config_problem("f16_deep_k", dist="int")
     C = run_gpu("f16", Ai, Bi, la, lb)
     check_integer_sums(C, Ai, Bi)
+
+
+# Sizes the paper itself evaluates (Section 5: the 1536 x 1024 x 2048 "NT" case of its first
+# experiment, and powers of two from the small (<= 1024) and large (1024..4096) ranges of its
+# last one), with the automatic tile selection.
+PAPER_SHAPES = [("f16", 1536, 1024, 2048, "NT"), ("f16", 256, 256, 256, "NT"), ("f16", 512, 1024, 256, "TN"),
+                ("f16", 1024, 1024, 1024, "NN"), ("f16", 2048, 1024, 4096, "TT"), ("f32", 1024, 512, 2048, "NT"),
+                ("f32", 512, 512, 512, "TN")]
+
+
+@pytest.mark.parametrize("case", PAPER_SHAPES, ids=lambda c: "%s_%dx%dx%d_%s" % c)
+def test_paper_sizes(oracle, case):
+    dtype, M, N, K, layout = case
+    la, lb = gi.LAYOUTS[layout]
+    A, B = gi.make_problem(600 + M + N + K, M, N, K, "uniform", dtype)
+    ref = oracle.gemm(M, N, K, A, 0, B, 0, dtype)
+    check(run_gpu(dtype, A, B, la, lb), ref, A, B, dtype, str(case))
+    Ai, Bi = gi.make_problem(601 + M + N + K, M, N, K, "int", dtype)
+    refi = oracle.gemm(M, N, K, Ai, 0, Bi, 0, dtype).astype(np.float32)
+    assert np.array_equal(run_gpu(dtype, Ai, Bi, la, lb), refi), case
