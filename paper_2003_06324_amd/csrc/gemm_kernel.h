@@ -175,6 +175,24 @@ struct DirectLoader {
                      : "memory", "m0");
     }
 
+    // Same load with the LDS destination split into a per-wave run-time part (LDS address
+    // of the ring + wave * 1024, held in a scalar register) and a compile-time byte offset
+    // OFF of the slot inside the ring: M0 is then set with a single scalar add of an
+    // immediate, and the K loop spends no other scalar work on LDS addresses.
+    template <int OFF>
+    __device__ __forceinline__ void issue_at(uint32_t wave_lds, int i)
+    {
+        int4_t rsrc;
+        rsrc[0] = (int)(uint32_t)(uintptr_t)base;
+        rsrc[1] = (int)(uint32_t)((uintptr_t)base >> 32) & 0xffff;
+        rsrc[2] = 0x7fffffff;
+        rsrc[3] = 0x00020000;
+        asm volatile("s_add_i32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
+                     :
+                     : "s"(wave_lds), "i"(OFF + i * NW * 1024), "v"(off[i]), "s"(rsrc)
+                     : "memory", "m0", "scc");
+    }
+
     // move to the next slab if `more`, else stay (branch-free)
     __device__ __forceinline__ void advance(bool more) { base += more ? step : 0; }
 };
@@ -450,6 +468,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 #pragma unroll
         for (int m = 0; m < NB; ++m) {
             mma(acc[m / FN][m % FN], ca[m / FN], cb[m % FN]);
+            // An MFMA is a pure operation to the optimiser, which would otherwise be free to
+            // sink it below the fetches and loads that follow; the empty volatile asm is an
+            // ordered use of the result and keeps the MFMA at this place in the stream.
+            asm volatile("" : "+a"(acc[m / FN][m % FN]));
             if (fetch) {
 #pragma unroll
                 for (int f = 0; f < NF; ++f) {
@@ -493,6 +515,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             DirectLoader<T, BN, NW, BKC> lb;
             la.init(A, p.lda, m0, p.M, k_done, wave, lane);
             lb.init(B, p.ldb, n0, p.N, k_done, wave, lane);
+            // The slot numbers repeat every NSLOT tiles, so the loop over tiles is unrolled
+            // NSLOT times with every LDS address a compile-time constant (operand fetches
+            // become base register + immediate, M0 values one scalar add).  With one wave per
+            // SIMD every instruction between two MFMAs competes for that wave's issue slots
+            // (about eight per 32-cycle MFMA), so address arithmetic in the loop shows up as
+            // idle matrix cores.  What is left over after whole groups of NSLOT tiles runs
+            // with slot numbers computed at run time.
+            const uint32_t wave_lds = (uint32_t)(uintptr_t)lds + wave * 1024;
             // A(0) B(0) A(1) B(1); the loaders then point at tile 2 (or the last tile)
             la.issue(lds + 0 * SLOT, wave);
             la.advance(1 < n);
@@ -506,18 +536,56 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             barrier_keep_loads();
 
             frag_t fa[2][FM], fb[2][FN];
-            fa[0][0] = Fetch<T, BM, AKC>::get(lds, wm * TM, 0, lane);
+            {
+                const GEMM_LDS(char) *cA = lds, *cB = lds + SLOT;
+                fa[0][0] = Fetch<T, BM, AKC>::get(cA, wm * TM, 0, lane);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) fb[0][j] = Fetch<T, BN, BKC>::get(lds + SLOT, wn * TN + j * 32, 0, lane);
+                for (int j = 0; j < FN; ++j) fb[0][j] = Fetch<T, BN, BKC>::get(cB, wn * TN + j * 32, 0, lane);
 #pragma unroll
-            for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(lds, wm * TM + i * 32, 0, lane);
+                for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(cA, wm * TM + i * 32, 0, lane);
+            }
+            // One steady-state tile with A(t) in slot SA.
+            auto tile_body = [&](auto sa_tag, const bool more) {
+                constexpr int SA = decltype(sa_tag)::value;
+                constexpr int O0 = ((SA + 0) % NSLOT) * SLOT, O1 = ((SA + 1) % NSLOT) * SLOT;
+                constexpr int O2 = ((SA + 2) % NSLOT) * SLOT, O3 = ((SA + 3) % NSLOT) * SLOT;
+                constexpr int O4 = ((SA + 4) % NSLOT) * SLOT;
+                const GEMM_LDS(char) *cA = lds + O0, *cB = lds + O1, *nA = lds + O2, *nB = lds + O3;
+                auto load_a_lo = [&](int q) { la.template issue_at<O4>(wave_lds, q); };
+                auto load_a_hi = [&](int q) { la.template issue_at<O4>(wave_lds, NVA / 2 + q); };
+                auto load_b = [&](int q) { lb.template issue_at<O0>(wave_lds, q); };
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, load_a_lo, std::integral_constant<int, NVA / 2>());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, load_a_hi, std::integral_constant<int, NVA - NVA / 2>());
+                la.advance(more);
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
+                // tile t+1 landed (all but the youngest NVA loads), own reads of tile t done
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVA));
+                barrier_keep_loads();
+                kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_b, std::integral_constant<int, NVB>());
+                lb.advance(more);
+            };
+            static_assert(NSLOT == 5, "the slot sequence below is 0 2 4 1 3");
+            // Constant addresses for five slots cost address registers (one base per 64 KiB of
+            // immediate-offset range and per lane pattern); the 8-wave tiles, with 128 vector
+            // registers per wave, would spill them, so they keep run-time slot numbers throughout.
+            constexpr bool CONST_SLOTS = NW <= 4;
+            const int nbody = n - 1;  // tiles 0 .. n-2 run a tile body, tile n-1 has nothing to load
+            int t = 0;
+            for (; CONST_SLOTS && t + NSLOT <= nbody; t += NSLOT) {
+                tile_body(std::integral_constant<int, 0>(), t + 3 < n);
+                tile_body(std::integral_constant<int, 2>(), t + 4 < n);
+                tile_body(std::integral_constant<int, 4>(), t + 5 < n);
+                tile_body(std::integral_constant<int, 1>(), t + 6 < n);
+                tile_body(std::integral_constant<int, 3>(), t + 7 < n);
+            }
+            // the remaining (n - 1) % NSLOT bodies and the last tile, slot numbers at run time
             int sa = 0;  // slot of A(t); B(t) is in the next one
             auto slot = [&](int d) -> GEMM_LDS(char) * {
                 int x = sa + d;
                 x = x >= NSLOT ? x - NSLOT : x;
                 return lds + x * SLOT;
             };
-            for (int t = 0; t < n - 1; ++t) {
+            for (; t < nbody; ++t) {
                 const GEMM_LDS(char) *cA = slot(0), *cB = slot(1);
                 const GEMM_LDS(char) *nA = slot(2), *nB = slot(3);
                 GEMM_LDS(char) *spare = slot(4);
@@ -528,7 +596,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, load_a_hi, std::integral_constant<int, NVA - NVA / 2>());
                 la.advance(t + 3 < n);
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
-                // tile t+1 landed (all but the youngest NVA loads), own reads of tile t done
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVA));
                 barrier_keep_loads();
                 kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_b, std::integral_constant<int, NVB>());
