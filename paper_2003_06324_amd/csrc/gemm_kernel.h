@@ -109,8 +109,11 @@ struct DirectLoader {
     // Address of a lane's granule = wave-uniform base (scalar registers, advanced per slab)
     // + a 32-bit per-lane byte offset that never changes.  The loads are buffer loads
     // (scalar resource descriptor + vector offset), so the K loop spends no vector
-    // instructions on pointers.
-    const char *base;
+    // instructions on pointers.  The base lives in the descriptor itself: words 0 and 1 are
+    // the 48-bit address (stride and swizzle bits above it are zero), word 2 a 2 GiB window
+    // (every offset used is below it and inside the operand by construction), word 3 the
+    // 32-bit data format.
+    int4_t rsrc;
     uint32_t off[PER_WAVE];
     int64_t step;  // bytes to advance per slab
 
@@ -120,7 +123,12 @@ struct DirectLoader {
     __device__ __forceinline__ void init(const T *origin, int64_t ld, int row0, int rmax, int k0,
                                          int wave, int lane)
     {
-        base = (const char *)(KC ? origin + (int64_t)row0 * ld + k0 : origin + (int64_t)k0 * ld + row0);
+        const uint64_t base =
+            (uint64_t)(uintptr_t)(KC ? origin + (int64_t)row0 * ld + k0 : origin + (int64_t)k0 * ld + row0);
+        rsrc[0] = (int)(uint32_t)base;
+        rsrc[1] = (int)(uint32_t)(base >> 32) & 0xffff;
+        rsrc[2] = 0x7fffffff;
+        rsrc[3] = 0x00020000;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + i * NW;
@@ -161,13 +169,6 @@ struct DirectLoader {
         // (counted vmcnt waits + barrier).  The compiler's own vmcnt waits stay safe: loads
         // complete in order, so extra outstanding loads only make a counted wait stricter.
         const int j = wave + i * NW;
-        // raw buffer descriptor: base, no stride, 2 GiB window (every offset used is below it
-        // and inside the operand by construction), 32-bit data format word
-        int4_t rsrc;
-        rsrc[0] = (int)(uint32_t)(uintptr_t)base;
-        rsrc[1] = (int)(uint32_t)((uintptr_t)base >> 32) & 0xffff;
-        rsrc[2] = 0x7fffffff;
-        rsrc[3] = 0x00020000;
         const uint32_t lds_addr = (uint32_t)(uintptr_t)(dst + j * 1024);
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                      :
@@ -182,11 +183,6 @@ struct DirectLoader {
     template <int OFF>
     __device__ __forceinline__ void issue_at(uint32_t wave_lds, int i)
     {
-        int4_t rsrc;
-        rsrc[0] = (int)(uint32_t)(uintptr_t)base;
-        rsrc[1] = (int)(uint32_t)((uintptr_t)base >> 32) & 0xffff;
-        rsrc[2] = 0x7fffffff;
-        rsrc[3] = 0x00020000;
         asm volatile("s_add_i32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
                      :
                      : "s"(wave_lds), "i"(OFF + i * NW * 1024), "v"(off[i]), "s"(rsrc)
@@ -194,7 +190,13 @@ struct DirectLoader {
     }
 
     // move to the next slab if `more`, else stay (branch-free)
-    __device__ __forceinline__ void advance(bool more) { base += more ? step : 0; }
+    __device__ __forceinline__ void advance(bool more)
+    {
+        uint64_t base = ((uint64_t)(uint32_t)rsrc[1] << 32) | (uint32_t)rsrc[0];
+        base += more ? step : 0;
+        rsrc[0] = (int)(uint32_t)base;
+        rsrc[1] = (int)(uint32_t)(base >> 32);
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -571,14 +573,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             constexpr bool CONST_SLOTS = NW <= 4;
             const int nbody = n - 1;  // tiles 0 .. n-2 run a tile body, tile n-1 has nothing to load
             int t = 0;
-            for (; CONST_SLOTS && t + NSLOT <= nbody; t += NSLOT) {
-                tile_body(std::integral_constant<int, 0>(), t + 3 < n);
-                tile_body(std::integral_constant<int, 2>(), t + 4 < n);
-                tile_body(std::integral_constant<int, 4>(), t + 5 < n);
-                tile_body(std::integral_constant<int, 1>(), t + 6 < n);
-                tile_body(std::integral_constant<int, 3>(), t + 7 < n);
+            // whole groups whose loaders all still advance (tile t + 4 fetches tile t + 6 < n)
+            for (; CONST_SLOTS && t + NSLOT + 2 < n; t += NSLOT) {
+                tile_body(std::integral_constant<int, 0>(), true);
+                tile_body(std::integral_constant<int, 2>(), true);
+                tile_body(std::integral_constant<int, 4>(), true);
+                tile_body(std::integral_constant<int, 1>(), true);
+                tile_body(std::integral_constant<int, 3>(), true);
             }
-            // the remaining (n - 1) % NSLOT bodies and the last tile, slot numbers at run time
+            // the remaining bodies and the last tile, slot numbers at run time
             int sa = 0;  // slot of A(t); B(t) is in the next one
             auto slot = [&](int d) -> GEMM_LDS(char) * {
                 int x = sa + d;
