@@ -661,6 +661,33 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     // epilogue: accumulator register r of lane l holds
     //   row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 block
     float *C = p.C + (int64_t)blockIdx.y * p.split_stride;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc does not know the buffer builtins
+    // Tiles that lie fully inside C (and whose byte offsets fit 32 bits) store through a
+    // buffer descriptor based at the tile origin: the per-lane part of the address is one
+    // 32-bit register, the row (i, r) a scalar offset and the column block j an immediate,
+    // so a store costs an accumulator read, a scalar multiply shared by FN stores, and the
+    // store itself - no per-store 64-bit address arithmetic, compares or exec masking.
+    if (m0 + BM <= p.M && n0 + BN <= p.N && p.ldc < (int64_t(1) << 20)) {
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void *)(C + (int64_t)m0 * p.ldc + n0), 0, 0x7fffffff, 0x00020000);
+        const int ldc4 = (int)p.ldc * 4;
+        const int voff = (wm * TM + 4 * (lane >> 5)) * ldc4 + (wn * TN + (lane & 31)) * 4;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int soff = (i * 32 + 8 * (r >> 2) + (r & 3)) * ldc4;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    // through a scalar temporary: a bit cast applied directly to a vector
+                    // element expression reads element 0 with this compiler
+                    const float v = acc[i][j][r];
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc, voff + j * 128, soff, 0);
+                }
+            }
+        return;
+    }
+#endif
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
 #pragma unroll
