@@ -525,46 +525,72 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             // idle matrix cores.  What is left over after whole groups of NSLOT tiles runs
             // with slot numbers computed at run time.
             const uint32_t wave_lds = (uint32_t)(uintptr_t)lds + wave * 1024;
-            // A(0) B(0) A(1) B(1); the loaders then point at tile 2 (or the last tile)
-            la.issue(lds + 0 * SLOT, wave);
-            la.advance(1 < n);
-            lb.issue(lds + 1 * SLOT, wave);
-            lb.advance(1 < n);
-            la.issue(lds + 2 * SLOT, wave);
-            la.advance(2 < n);
-            lb.issue(lds + 3 * SLOT, wave);
-            lb.advance(2 < n);
+            // Ring order: the operand called X here goes first (X(0) Y(0) X(1) Y(1) ...), is
+            // prefetched two tiles ahead into the spare slot and so has the longer time to
+            // land; Y follows one tile ahead.  Which operand should be X is a measured choice:
+            // B first gains 4-13% for the binary16 256x256 and 64x64 tiles on data that does
+            // not throttle the clock, and loses 1-2% for the 128x128 tile and for binary32.
+            constexpr bool BF = sizeof(T) == 2 && BM != 128;
+            constexpr int PA = BF ? 1 : 0, PB = 1 - PA;  // position of A and B in a tile's slot pair
+            constexpr int NVX = BF ? NVB : NVA, NVY = BF ? NVA : NVB;  // loads per wave and slab
+            auto x_issue = [&](GEMM_LDS(char) *dst, int q) { if constexpr (BF) lb.issue1(dst, wave, q); else la.issue1(dst, wave, q); };
+            auto y_issue = [&](GEMM_LDS(char) *dst, int q) { if constexpr (BF) la.issue1(dst, wave, q); else lb.issue1(dst, wave, q); };
+            auto x_advance = [&](bool more) { if constexpr (BF) lb.advance(more); else la.advance(more); };
+            auto y_advance = [&](bool more) { if constexpr (BF) la.advance(more); else lb.advance(more); };
+            // X(0) Y(0) X(1) Y(1); the loaders then point at tile 2 (or the last tile)
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+#pragma unroll
+                for (int q = 0; q < (h % 2 == 0 ? NVX : NVY); ++q) {
+                    if (h % 2 == 0) x_issue(lds + h * SLOT, q);
+                    else y_issue(lds + h * SLOT, q);
+                }
+                if (h % 2 == 0) x_advance(h / 2 + 1 < n);
+                else y_advance(h / 2 + 1 < n);
+            }
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(NVA + NVB));  // tile 0 landed
             barrier_keep_loads();
 
             frag_t fa[2][FM], fb[2][FN];
             {
-                const GEMM_LDS(char) *cA = lds, *cB = lds + SLOT;
+                const GEMM_LDS(char) *cA = lds + PA * SLOT, *cB = lds + PB * SLOT;
                 fa[0][0] = Fetch<T, BM, AKC>::get(cA, wm * TM, 0, lane);
 #pragma unroll
                 for (int j = 0; j < FN; ++j) fb[0][j] = Fetch<T, BN, BKC>::get(cB, wn * TN + j * 32, 0, lane);
 #pragma unroll
                 for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(cA, wm * TM + i * 32, 0, lane);
             }
-            // One steady-state tile with A(t) in slot SA.
+            // The k-groups of one steady-state tile; cX.. are the slots of this and the next tile.
+            auto tile_kgroups = [&](const GEMM_LDS(char) * cA, const GEMM_LDS(char) * cB, const GEMM_LDS(char) * nA,
+                                    const GEMM_LDS(char) * nB, auto load_x_lo, auto load_x_hi, auto load_y,
+                                    const bool more) {
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, load_x_lo, std::integral_constant<int, NVX / 2>());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, load_x_hi, std::integral_constant<int, NVX - NVX / 2>());
+                x_advance(more);
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
+                // tile t+1 landed (all but the youngest NVX loads), own reads of tile t done
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVX));
+                barrier_keep_loads();
+                kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_y, std::integral_constant<int, NVY>());
+                y_advance(more);
+            };
+            // One steady-state tile whose slot pair starts at slot SA (compile time).
             auto tile_body = [&](auto sa_tag, const bool more) {
                 constexpr int SA = decltype(sa_tag)::value;
                 constexpr int O0 = ((SA + 0) % NSLOT) * SLOT, O1 = ((SA + 1) % NSLOT) * SLOT;
                 constexpr int O2 = ((SA + 2) % NSLOT) * SLOT, O3 = ((SA + 3) % NSLOT) * SLOT;
                 constexpr int O4 = ((SA + 4) % NSLOT) * SLOT;
-                const GEMM_LDS(char) *cA = lds + O0, *cB = lds + O1, *nA = lds + O2, *nB = lds + O3;
-                auto load_a_lo = [&](int q) { la.template issue_at<O4>(wave_lds, q); };
-                auto load_a_hi = [&](int q) { la.template issue_at<O4>(wave_lds, NVA / 2 + q); };
-                auto load_b = [&](int q) { lb.template issue_at<O0>(wave_lds, q); };
-                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, load_a_lo, std::integral_constant<int, NVA / 2>());
-                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, load_a_hi, std::integral_constant<int, NVA - NVA / 2>());
-                la.advance(more);
-                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
-                // tile t+1 landed (all but the youngest NVA loads), own reads of tile t done
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVA));
-                barrier_keep_loads();
-                kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_b, std::integral_constant<int, NVB>());
-                lb.advance(more);
+                auto load_x_lo = [&](int q) {
+                    if constexpr (BF) lb.template issue_at<O4>(wave_lds, q); else la.template issue_at<O4>(wave_lds, q);
+                };
+                auto load_x_hi = [&](int q) {
+                    if constexpr (BF) lb.template issue_at<O4>(wave_lds, NVX / 2 + q); else la.template issue_at<O4>(wave_lds, NVX / 2 + q);
+                };
+                auto load_y = [&](int q) {
+                    if constexpr (BF) la.template issue_at<O0>(wave_lds, q); else lb.template issue_at<O0>(wave_lds, q);
+                };
+                tile_kgroups(lds + (PA ? O1 : O0), lds + (PB ? O1 : O0), lds + (PA ? O3 : O2), lds + (PB ? O3 : O2),
+                             load_x_lo, load_x_hi, load_y, more);
             };
             static_assert(NSLOT == 5, "the slot sequence below is 0 2 4 1 3");
             // Constant addresses for five slots cost address registers (one base per 64 KiB of
@@ -582,31 +608,22 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 tile_body(std::integral_constant<int, 3>(), true);
             }
             // the remaining bodies and the last tile, slot numbers at run time
-            int sa = 0;  // slot of A(t); B(t) is in the next one
+            int sa = 0;  // first slot of tile t's pair
             auto slot = [&](int d) -> GEMM_LDS(char) * {
                 int x = sa + d;
                 x = x >= NSLOT ? x - NSLOT : x;
                 return lds + x * SLOT;
             };
             for (; t < nbody; ++t) {
-                const GEMM_LDS(char) *cA = slot(0), *cB = slot(1);
-                const GEMM_LDS(char) *nA = slot(2), *nB = slot(3);
-                GEMM_LDS(char) *spare = slot(4);
-                auto load_a_lo = [&](int q) { la.issue1(spare, wave, q); };
-                auto load_a_hi = [&](int q) { la.issue1(spare, wave, NVA / 2 + q); };
-                auto load_b = [&](int q) { lb.issue1((GEMM_LDS(char) *)cA, wave, q); };
-                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, load_a_lo, std::integral_constant<int, NVA / 2>());
-                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, load_a_hi, std::integral_constant<int, NVA - NVA / 2>());
-                la.advance(t + 3 < n);
-                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVA));
-                barrier_keep_loads();
-                kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_b, std::integral_constant<int, NVB>());
-                lb.advance(t + 3 < n);
+                GEMM_LDS(char) *s0 = slot(0), *spare = slot(4);
+                auto load_x_lo = [&](int q) { x_issue(spare, q); };
+                auto load_x_hi = [&](int q) { x_issue(spare, NVX / 2 + q); };
+                auto load_y = [&](int q) { y_issue(s0, q); };
+                tile_kgroups(slot(PA), slot(PB), slot(2 + PA), slot(2 + PB), load_x_lo, load_x_hi, load_y, t + 3 < n);
                 sa = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
             }
             {
-                const GEMM_LDS(char) *cA = slot(0), *cB = slot(1);
+                const GEMM_LDS(char) *cA = slot(PA), *cB = slot(PB);
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
                 kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
