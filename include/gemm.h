@@ -20,8 +20,9 @@
  *   (r,c) of a row-major matrix is at index r*ld + c, of a column-major matrix
  *   at r + c*ld (indices in elements).  ld == 0 means packed (row-major: number
  *   of columns, column-major: number of rows); otherwise ld must be at least
- *   that value.  Elements between the packed extent and ld are never read or
- *   written.  Pointers need only element alignment; 16-byte aligned bases with
+ *   that value.  Elements between the packed extent and ld are never written.
+ *   Those of A and B may be read (nothing past an operand's last element is),
+ *   but their values, NaN included, never influence C.  Pointers need only element alignment; 16-byte aligned bases with
  *   leading dimensions that are multiples of 16 bytes take the fastest kernels.
  *
  * Element types

@@ -219,7 +219,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     if (!bkc && N % EPC != 0) aligned = false;
 
     // the direct loaders address a tile with 32-bit byte offsets from its origin
-    if (256 * lda * (int64_t)sizeof(T) >= (1LL << 31) || 256 * ldb * (int64_t)sizeof(T) >= (1LL << 31)) aligned = false;
+    const bool ld32 = 256 * lda * (int64_t)sizeof(T) < (1LL << 31) && 256 * ldb * (int64_t)sizeof(T) < (1LL << 31);
+    if (!ld32) aligned = false;
 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
@@ -244,6 +245,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.tiles_m = (int)tiles_m;
     a.tiles_n = (int)tiles_n;
     a.kt_per_split = (int)kt_per_split;
+    a.ld32 = ld32 ? 1 : 0;
     void *ws = nullptr;
     if (splits > 1) {
         const int rc = get_workspace((size_t)splits * (size_t)M * (size_t)N * sizeof(float), &ws);

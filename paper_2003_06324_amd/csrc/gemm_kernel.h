@@ -64,6 +64,7 @@ struct KernelArgs {
     int M, N, K;
     int tiles_m, tiles_n;
     int kt_per_split;    // slabs per K-slice (blockIdx.y selects the slice)
+    int ld32;            // 256 * ld * sizeof(element) < 2^31 for A and B: tile-local byte offsets fit 32 bits
 };
 
 template <typename T> struct Elem;
@@ -187,6 +188,23 @@ struct DirectLoader {
                      :
                      : "s"(wave_lds), "i"(OFF + i * NW * 1024), "v"(off[i]), "s"(rsrc)
                      : "memory", "m0", "scc");
+    }
+
+    // The same granule through a register instead (operands whose rows are not 16-byte
+    // aligned cannot use the direct loads): a 16-byte load that needs element alignment only,
+    // and the store that puts it where the direct load would have put it.
+    __device__ __forceinline__ uint4_t fetch1(int i) const
+    {
+        // a global-address-space pointer (a generic one would make this a flat load, which
+        // also counts as an LDS operation and would be waited for at every operand fetch)
+        typedef uint4_t granule_t __attribute__((aligned(2)));  // element alignment of the narrower type
+        typedef const __attribute__((address_space(1))) char *gptr_t;
+        const gptr_t base = (gptr_t)(uintptr_t)(((uint64_t)(uint32_t)rsrc[1] << 32) | (uint32_t)rsrc[0]);
+        return *(const __attribute__((address_space(1))) granule_t *)(base + off[i]);
+    }
+    __device__ __forceinline__ void store1(GEMM_LDS(char) *dst, int wave, int lane, int i, const uint4_t &w) const
+    {
+        *(GEMM_LDS(uint4_t) *)(dst + (wave + i * NW) * 1024 + lane * 16) = w;
     }
 
     // move to the next slab if `more`, else stay (branch-free)
@@ -393,7 +411,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be built from 32x32 blocks");
     constexpr int A_BYTES = BM * RBK, B_BYTES = BN * RBK;
     constexpr int SLOT = A_BYTES > B_BYTES ? A_BYTES : B_BYTES;  // one operand slab
-    constexpr int NBUF = ALIGNED ? NSLOT : 2;
+    constexpr int NBUF = ALIGNED ? NSLOT : 4;  // ring of five operand slots, or two buffers of (A, B)
     typedef typename Frag<T>::type frag_t;
     // LDS reads and MFMAs per k-group (for the interleave hints)
     constexpr int RD_A = sizeof(T) == 2 ? (AKC ? 1 : 2) : (AKC ? 1 : 4);
@@ -496,6 +514,19 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     typedef std::integral_constant<int, 0> L0;
 
     int k_done = kt0 * BK;  // first k not yet accumulated
+    // Registers of the guarded loop at the end.  When a fast path is followed by leftover k
+    // (a ragged tail), it fetches the first leftover slab into them before its own last slab
+    // is multiplied, so that the loads are not waited for in the open.
+    Staged<T, BM, NT> sa_;
+    Staged<T, BN, NT> sb_;
+    bool staged_ready = false;
+    auto prefetch_leftover = [&](int k_from) {
+        if (k_from < kend) {
+            guarded_fetch<T, BM, NT, AKC>(sa_, A, p.lda, m0, p.M, k_from, kend, tid);
+            guarded_fetch<T, BN, NT, BKC>(sb_, B, p.ldb, n0, p.N, k_from, kend, tid);
+            staged_ready = true;
+        }
+    };
     if (ALIGNED) {
         // Full slabs: direct global->LDS loads into a ring of NSLOT = 5 operand slots.
         // Operand slabs are fetched in the order A(0) B(0) A(1) B(1) ..., slab number h going
@@ -622,6 +653,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 tile_kgroups(slot(PA), slot(PB), slot(2 + PA), slot(2 + PB), load_x_lo, load_x_hi, load_y, t + 3 < n);
                 sa = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
             }
+            prefetch_leftover(k_done + n * BK);
             {
                 const GEMM_LDS(char) *cA = slot(PA), *cB = slot(PB);
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
@@ -633,15 +665,96 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant refills
         }
     }
-    // Remaining slabs (a ragged tail, or everything when operands are unaligned): guarded
+    if (!ALIGNED) {
+        // Operands that are not 16-byte aligned: full slabs go through registers into two LDS
+        // buffers (the same image as the direct loads make).  Per slab s: k-groups 0,1 multiply;
+        // k-group 2 also writes slab s+1 (in registers since the previous slab) to the other
+        // buffer; wait for the own LDS traffic, one barrier; k-group 3 also issues the global
+        // loads of slab s+2 into the freed registers and fetches slab s+1's first operands.
+        // Rows (or whole granules) past the M/N edge re-read a valid one as in the direct
+        // path.  A granule of an M/N-contiguous operand that straddles the edge is read whole:
+        // its tail is the padding or the start of the next k-row, lands in tile rows past the
+        // edge and only feeds results that are never stored.  On the operand's last k-row
+        // that tail could lie past the end of the operand, so a tile with such granules leaves
+        // the slab that holds the last k-row to the guarded loop below, which also takes
+        // leading dimensions shorter than two granules or too long for 32-bit offsets.
+        constexpr int EPC = Elem<T>::EPC;
+        const bool edge_a = !AKC && p.M % EPC != 0 && m0 + BM > p.M;
+        const bool edge_b = !BKC && p.N % EPC != 0 && n0 + BN > p.N;
+        const bool narrow = (edge_a && p.lda < 2 * EPC) || (edge_b && p.ldb < 2 * EPC);
+        int n = (kend - k_done) / BK;
+        if ((edge_a || edge_b) && k_done + n * BK == p.K) --n;
+        if (n > 0 && p.ld32 && !narrow) {
+            DirectLoader<T, BM, NW, AKC> la;
+            DirectLoader<T, BN, NW, BKC> lb;
+            la.init(A, p.lda, m0, p.M, k_done, wave, lane);
+            lb.init(B, p.ldb, n0, p.N, k_done, wave, lane);
+            uint4_t ra[NVA], rb[NVB];
+            auto fetch_regs = [&](int q) {
+                if (q < NVA) ra[q] = la.fetch1(q);
+                else rb[q - NVA] = lb.fetch1(q - NVA);
+            };
+            GEMM_LDS(char) *wA = lds, *wB = lds + SLOT;  // where the registers go next
+            auto store_regs = [&](int q) {
+                if (q < NVA) la.store1(wA, wave, lane, q, ra[q]);
+                else lb.store1(wB, wave, lane, q - NVA, rb[q - NVA]);
+            };
+            typedef std::integral_constant<int, NVA + NVB> LAB;
+#pragma unroll
+            for (int q = 0; q < NVA + NVB; ++q) fetch_regs(q);
+            la.advance(1 < n);
+            lb.advance(1 < n);
+#pragma unroll
+            for (int q = 0; q < NVA + NVB; ++q) store_regs(q);
+#pragma unroll
+            for (int q = 0; q < NVA + NVB; ++q) fetch_regs(q);
+            la.advance(2 < n);
+            lb.advance(2 < n);
+            __syncthreads();
+
+            frag_t fa[2][FM], fb[2][FN];
+            fa[0][0] = Fetch<T, BM, AKC>::get(lds, wm * TM, 0, lane);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[0][j] = Fetch<T, BN, BKC>::get(lds + SLOT, wn * TN + j * 32, 0, lane);
+#pragma unroll
+            for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(lds, wm * TM + i * 32, 0, lane);
+            int cur = 0;
+            for (int sl = 0; sl < n - 1; ++sl) {
+                const GEMM_LDS(char) *cA = lds + (2 * cur) * SLOT, *cB = cA + SLOT;
+                wA = lds + (2 * (cur ^ 1)) * SLOT;
+                wB = wA + SLOT;
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, store_regs, LAB());
+                // own LDS writes and reads done; the loads issued below stay in flight
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
+                barrier_keep_loads();
+                kgroup(fa[1], fb[1], fa[0], fb[0], wA, wB, 0, true, fetch_regs, LAB());
+                la.advance(sl + 3 < n);
+                lb.advance(sl + 3 < n);
+                cur ^= 1;
+            }
+            prefetch_leftover(k_done + n * BK);
+            {
+                const GEMM_LDS(char) *cA = lds + (2 * cur) * SLOT, *cB = cA + SLOT;
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
+                kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 0, false, no_load, L0());
+            }
+            k_done += n * BK;
+            // the redundant last refill is still in flight: it targets registers only
+        }
+    }
+    // Remaining slabs (a ragged K tail; everything for the tiles excluded above): guarded
     // loads through registers into one LDS buffer; the loads of slab s+1 are issued before
     // slab s is multiplied and written to LDS after it.
     if (k_done < kend) {
-        Staged<T, BM, NT> sa_;
-        Staged<T, BN, NT> sb_;
         __syncthreads();  // LDS is free (direct-load pipeline drained, all reads done)
-        guarded_fetch<T, BM, NT, AKC>(sa_, A, p.lda, m0, p.M, k_done, kend, tid);
-        guarded_fetch<T, BN, NT, BKC>(sb_, B, p.ldb, n0, p.N, k_done, kend, tid);
+        if (!staged_ready) {
+            guarded_fetch<T, BM, NT, AKC>(sa_, A, p.lda, m0, p.M, k_done, kend, tid);
+            guarded_fetch<T, BN, NT, BKC>(sb_, B, p.ldb, n0, p.N, k_done, kend, tid);
+        }
         staged_store<T, BM, NT, AKC>(lds, sa_, A, p.lda, m0, p.M, k_done, kend, tid);
         staged_store<T, BN, NT, BKC>(lds + SLOT, sb_, B, p.ldb, n0, p.N, k_done, kend, tid);
         __syncthreads();
@@ -700,6 +813,33 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                     // element expression reads element 0 with this compiler
                     const float v = acc[i][j][r];
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc, voff + j * 128, soff, 0);
+                }
+            }
+        return;
+    }
+    // Edge tiles, same descriptor trick: the descriptor's range ends with the last valid row
+    // (out-of-range buffer stores are discarded by the hardware) and lanes whose column is
+    // past N get an offset that is out of range by itself.  The row offset goes into the
+    // vector offset here, because the range check does not look at the scalar offset.
+    if (p.ldc < (int64_t(1) << 20)) {
+        const int ldc4 = (int)p.ldc * 4;
+        const int rows_valid = p.M - m0 < BM ? p.M - m0 : BM;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void *)(C + (int64_t)m0 * p.ldc + n0), 0, rows_valid * ldc4, 0x00020000);
+        const int voff = (wm * TM + 4 * (lane >> 5)) * ldc4 + (wn * TN + (lane & 31)) * 4;
+        int voffj[FN];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            voffj[j] = n0 + wn * TN + j * 32 + (lane & 31) < p.N ? voff + j * 128 : (int)0x80000000;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int roff = (i * 32 + 8 * (r >> 2) + (r & 3)) * ldc4;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const float v = acc[i][j][r];
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc, voffj[j] + roff, 0, 0);
                 }
             }
         return;
