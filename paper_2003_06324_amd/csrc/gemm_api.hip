@@ -59,17 +59,17 @@ struct TileConfig {
     int wg_per_cu;              // resident workgroups per CU (LDS-limited)
     double f16_alone, f16_full; // microseconds per 64-k slab: one workgroup on a CU / CU fully occupied
     double f32_alone, f32_full; // same per 32-k f32 slab
-    double general;             // slowdown of the guarded (unaligned) path
+    double general;             // slowdown of the register-staged (unaligned) path
     launch_fn f16, f32;
 };
 
 // Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
 // under sustained MFMA load; these are not clock-peak figures).
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 2.0, 2.0, 7.9, 7.9, 1.85, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
-    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.8, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
-    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.55, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
-    {"t256x256w8", 256, 256, 1, 2.02, 2.02, 7.7, 7.7, 1.33, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>},
+    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
+    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
+    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
+    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -101,10 +101,10 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
     const double alone = f32 ? t.f32_alone : t.f16_alone, full = f32 ? t.f32_full : t.f16_full;
     double slab = alone + (t.wg_per_cu > 1 ? (full - alone) * (double)(share - 1) / (t.wg_per_cu - 1) : 0.0);
     if (!aligned) {
-        // the guarded path exposes one global-load round trip (~2.2 us) per slab, hidden only by
-        // the other workgroups on the CU
+        // the register-staged path prefetches one slab ahead only: a slab cannot take less than
+        // about one global-load round trip, shared among the workgroups on the CU
         slab *= t.general;
-        if (slab < 2.2 / (double)share) slab = 2.2 / (double)share;
+        if (slab < 1.2 / (double)share) slab = 1.2 / (double)share;
     }
     const double t_mfma = rounds * ((double)per * slab + 1.0);
     const double esz = f32 ? 4.0 : 2.0;
