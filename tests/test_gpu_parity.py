@@ -53,19 +53,58 @@ def test_integer_bit_exact_every_tile(oracle, dtype, tile):
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_k_loop_lengths(oracle, dtype):
-    # every K-loop trip count from a lone partial chunk to three chunks and a tail,
-    # on aligned and unaligned leading dimensions (double-buffer hand-over)
-    # bk = K-slab of the kernels; the direct-load ring is 4 slabs deep
-    bk = 32 if dtype == "f16" else 16
+    # every K-loop trip count from a lone partial slab up to 18 slabs and a tail, on aligned
+    # and unaligned leading dimensions: prologue only, the run-time-slot tiles, one, two and
+    # three groups of the loop that is unrolled over the five-slot ring, each with and
+    # without leftover tiles and a ragged tail (bk = K-slab of the kernels)
+    bk = 64 if dtype == "f16" else 32
     ks = [1, 2, 7, 8, bk - 1, bk, bk + 1, bk + 8, 2 * bk, 3 * bk + 8, 4 * bk, 4 * bk + 1, 5 * bk,
-          6 * bk + 16, 9 * bk, 13 * bk + 8]
+          6 * bk + 16, 7 * bk, 8 * bk, 8 * bk + 8, 9 * bk, 10 * bk, 11 * bk + 1, 12 * bk, 13 * bk + 8,
+          14 * bk, 17 * bk, 18 * bk + 24]
     for K in ks:
         A, B = gi.make_problem(900 + K, 136, 72, K, "int", dtype)
         ref = ref_of(oracle, A, B, dtype).astype(np.float32)
         for la, lb in LAYOUT_PAIRS:
-            for tile in ("t128x128", "t64x64", "t256x256w8"):
+            for tile in TILES:
                 C = run_gpu(dtype, A, B, la, lb, force=tile)
                 assert np.array_equal(C, ref), (dtype, K, la, lb, tile)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_unaligned_edges_and_last_k_row(oracle, dtype):
+    # Operands whose rows are not 16-byte aligned take the register-staged loop.  M or N not a
+    # multiple of the 16-byte granule makes granules of an M/N-contiguous operand straddle the
+    # matrix edge; K a multiple of the slab puts the operand's last k-row into a full slab
+    # (which such tiles must leave to the guarded loop); tiny leading dimensions and K slices
+    # on top.  Padding is NaN, so a value read from outside the matrix would show.
+    bk = 64 if dtype == "f16" else 32
+    shapes = [(300, 260, 4 * bk), (300, 260, 2 * bk), (77, 9, 3 * bk), (5, 7, 2 * bk), (12, 20, bk),
+              (264, 300, 9 * bk), (130, 67, 9 * bk + 5), (3, 2, 5 * bk)]
+    for (M, N, K) in shapes:
+        A, B = gi.make_problem(400 + M + K, M, N, K, "int", dtype)
+        ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for la, lb in LAYOUT_PAIRS:
+            for tile in TILES:
+                for splits, pads in ((1, (0, 0, 0)), (2, (0, 0, 0)), (1, (1, 3, 0)), (1, (2, 0, 1))):
+                    C, cfg = run_gpu(dtype, A, B, la, lb, pads=pads, force="%s:s%d" % (tile, splits),
+                                     return_config=True)
+                    assert np.array_equal(C, ref), (dtype, M, N, K, la, lb, tile, splits, pads, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_leading_dimension_beyond_32_bit_tile_offsets(oracle, dtype):
+    # 256 rows of such an operand span 2 GiB or more, so tile-local byte offsets do not fit
+    # 32 bits: neither the direct loads nor the register-staged loop may be used
+    ld = (1 << 31) // 256 // (2 if dtype == "f16" else 4)
+    M, N, K = 3, 70, 200
+    A, B = gi.make_problem(55, M, N, K, "int", dtype)
+    ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+    for extra in (0, 8, 3):
+        C, cfg = run_gpu(dtype, A, B, gi.ROW_MAJOR, gi.ROW_MAJOR, pads=(ld + extra - K, 0, 0), return_config=True)
+        assert "general" in cfg and np.array_equal(C, ref), (dtype, extra, cfg)
+        C, cfg = run_gpu(dtype, B.T.copy(), A.T.copy(), gi.COL_MAJOR, gi.COL_MAJOR, pads=(0, ld + extra - K, 0),
+                         return_config=True)
+        assert "general" in cfg and np.array_equal(C, ref.T), (dtype, extra, cfg)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
