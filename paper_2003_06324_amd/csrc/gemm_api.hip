@@ -230,9 +230,9 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     }
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
-    if (tiles_m * tiles_n > (1LL << 28)) return GEMM_ERR_UNSUPPORTED;
     int64_t kt_per_split = cdiv(KT, splits);
     splits = (int)cdiv(KT, kt_per_split);  // no empty slices
+    if (tiles_m * tiles_n * splits > (1LL << 28)) return GEMM_ERR_UNSUPPORTED;
 
     KernelArgs a;
     a.A = A;
@@ -245,6 +245,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.tiles_m = (int)tiles_m;
     a.tiles_n = (int)tiles_n;
     a.kt_per_split = (int)kt_per_split;
+    a.splits = splits;
     a.ld32 = ld32 ? 1 : 0;
     void *ws = nullptr;
     if (splits > 1) {
@@ -258,7 +259,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         a.ldc = ldc;
         a.split_stride = 0;
     }
-    const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n, 8)), (unsigned)splits);
+    const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n * splits, 8)));
     const launch_fn fn = f32 ? t.f32 : t.f16;
     const hipError_t launch_rc = fn(akc, bkc, aligned, grid, stream, a);
     if (launch_rc != hipSuccess) {

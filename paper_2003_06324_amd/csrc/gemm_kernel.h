@@ -63,7 +63,8 @@ struct KernelArgs {
     int64_t split_stride;  // elements between consecutive K-slices of the workspace
     int M, N, K;
     int tiles_m, tiles_n;
-    int kt_per_split;    // slabs per K-slice (blockIdx.y selects the slice)
+    int kt_per_split;    // slabs per K-slice
+    int splits;          // number of K-slices; the grid holds tiles_m * tiles_n * splits work items
     int ld32;            // 256 * ld * sizeof(element) < 2^31 for A and B: tile-local byte offsets fit 32 bits
 };
 
@@ -400,7 +401,7 @@ __device__ __forceinline__ void mma(float16_t &acc, const float4_t &a, const flo
 }
 
 // ---------------------------------------------------------------------------
-// The kernel.  grid.x = 8 * ceil(tiles/8) workgroups, grid.y = K-slices.
+// The kernel.  grid.x = 8 * ceil(tiles * K-slices / 8) workgroups.
 // ---------------------------------------------------------------------------
 template <typename T, int BM, int BN, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs p)
@@ -430,13 +431,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
-    // give every XCD one contiguous run of tiles, and order tiles in bands of
-    // GM tile rows so that tiles running together share A and B panels.
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every XCD
+    // one contiguous run of work items, K-slice by K-slice (the tiles of one slice share that
+    // slice's A and B panels; the same tile in another slice shares nothing), and within a
+    // slice order tiles in bands of GM tile rows so that tiles running together share panels.
     const int ntiles = p.tiles_m * p.tiles_n;
-    const int per_xcd = (ntiles + 7) >> 3;
-    const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (lin >= ntiles) return;
+    const int nwork = ntiles * p.splits;
+    const int per_xcd = (nwork + 7) >> 3;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= nwork) return;
+    const int slice = work / ntiles;
+    const int lin = work - slice * ntiles;
     constexpr int GM = 8;
     const int band = lin / (GM * p.tiles_n);
     const int first_m = band * GM;
@@ -448,7 +453,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 
     // K range of this slice
     const int KT = (p.K + BK - 1) / BK;
-    const int kt0 = blockIdx.y * p.kt_per_split;
+    const int kt0 = slice * p.kt_per_split;
     int kt1 = kt0 + p.kt_per_split;
     kt1 = kt1 < KT ? kt1 : KT;
     const int kend = (kt1 * BK) < p.K ? (kt1 * BK) : p.K;
@@ -790,7 +795,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 
     // epilogue: accumulator register r of lane l holds
     //   row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 block
-    float *C = p.C + (int64_t)blockIdx.y * p.split_stride;
+    float *C = p.C + (int64_t)slice * p.split_stride;
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc does not know the buffer builtins
     // Tiles that lie fully inside C (and whose byte offsets fit 32 bits) store through a
     // buffer descriptor based at the tile origin: the per-lane part of the address is one
