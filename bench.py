@@ -152,6 +152,15 @@ def main():
                  "tflops": round(z_tflops, 1), "frac_of_peak": round(z_tflops / PEAK_TFLOPS["f16"], 4)}
     del Z, CZ
 
+    # --- context: the binary16-output entry point on the NT case (the operand and result types of
+    # the paper's own tensor-core kernels and of the half-precision routine it is measured against)
+    C16 = torch.empty(S * S, dtype=torch.float16, device="cuda")
+    nt = calls[names.index("NT")]
+    _, pc16 = time_calls(g.gemm_f16f16, [nt[:9] + (C16,) + nt[10:]], max(5, args.steps // 2), max(2, args.warmup // 2))
+    fp16_out = {"workload": "f16f16_%dx%dx%d_NT (binary16 C)" % (S, S, S), "ms": round(pc16[0], 4),
+                "tflops": round(flop / pc16[0] / 1e9, 1), "kernel": g.last_config()}
+    del C16
+
     # --- secondary workload (not part of the timed step): FP32 4096^3, A row-major, B column-major
     A32_np, B32_np = gi.make_problem(2000, 4096, 4096, 4096, "uniform", "f32")
     A32 = torch.from_numpy(A32_np).cuda()
@@ -173,7 +182,7 @@ def main():
         "config": {"workload": "f16f32_%dx%dx%d_NN+NT+TN+TT" % (S, S, S), "gemms_per_step": 4,
                    "entries": "N(0,1) rounded to binary16, seed 3000", "C": "binary32 row-major"},
         "pct_of_peak": round(100.0 * value / PEAK_TFLOPS["f16"], 2),
-        "per_layout": per_layout, "roofline": roofline, "zero_data": zero_data, "fp32": fp32,
+        "per_layout": per_layout, "roofline": roofline, "zero_data": zero_data, "fp16_out": fp16_out, "fp32": fp32,
     }
     if not args.no_cpu_baseline:
         def gpu_rows(rows):

@@ -29,6 +29,7 @@
  *   gemm_f32    : binary32 operands, IEEE binary32 multiply-add, binary32 C.
  *   gemm_f16f32 : binary16 operands (passed as their 16-bit patterns), products
  *                 accumulated in binary32, binary32 C.
+ *   gemm_f16f16 : the same, with C rounded to binary16 at the store.
  *   The order in which the K products are added is unspecified.
  *
  * Execution
@@ -83,6 +84,20 @@ int gemm_f16f32(int64_t M, int64_t N, int64_t K,
                 const uint16_t *A, int layoutA, int64_t lda,
                 const uint16_t *B, int layoutB, int64_t ldb,
                 float *C, int layoutC, int64_t ldc,
+                void *hip_stream);
+
+/*
+ * C = A*B, binary16 operands, binary32 accumulation, binary16 result: the
+ * operand types of the paper's executable tensor-core spec (Section 4.2,
+ * "Supporting HMMA", where C is FP16 as well) and of the half-precision library
+ * routine it is measured against (Section 5.3).  Each element of C is the
+ * binary32 sum rounded once to binary16, to nearest even; sums beyond the
+ * binary16 range become infinities.  C is passed as 16-bit patterns.
+ */
+int gemm_f16f16(int64_t M, int64_t N, int64_t K,
+                const uint16_t *A, int layoutA, int64_t lda,
+                const uint16_t *B, int layoutB, int64_t ldb,
+                uint16_t *C, int layoutC, int64_t ldc,
                 void *hip_stream);
 
 /*

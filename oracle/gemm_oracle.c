@@ -34,7 +34,9 @@
  * Parity pins (tests marked "not gpu"): brute force in Python integers on
  * tiny shapes, identity and permutation operands, the transpose invariant,
  * small-integer inputs against an int64 loop, closed forms, and a float64
- * numpy.matmul cross-check.
+ * numpy.matmul cross-check; for the binary16 rounding: the round trip of all
+ * 65536 patterns, hand constants, exact midpoints (ties to even), the overflow
+ * and subnormal thresholds, and numpy's float64 -> float16 conversion.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -193,6 +195,47 @@ int oracle_gemm_f16_at(int64_t M, int64_t N, int64_t K,
                    oracle_half_bits_to_double(B[at(layoutB, ldb, k, cols[t])]);
         out[t] = acc;
     }
+    return 0;
+}
+
+/*
+ * double -> IEEE 754 binary16 bit pattern, rounded to nearest, ties to even: the single
+ * rounding the binary16-output entry point applies to each element of C (the operand
+ * types of the paper's executable tensor-core spec, Section 4.2 "Supporting HMMA",
+ * have C in FP16).  Written from the format's definition: normal numbers are
+ * (1 + f/1024) * 2^(e-15) with 1 <= e <= 30, subnormals f * 2^-24, and a magnitude that
+ * rounds to 2^16 or more is infinite.
+ */
+#include <math.h>
+uint16_t oracle_double_to_half_bits(double v)
+{
+    uint16_t sign = signbit(v) ? 0x8000u : 0u;
+    if (isnan(v)) return (uint16_t)(sign | 0x7e00u);
+    double a = fabs(v);
+    if (isinf(a)) return (uint16_t)(sign | 0x7c00u);
+    if (a == 0.0) return sign;
+    int ex;
+    double m = frexp(a, &ex); /* a = m * 2^ex, 0.5 <= m < 1 */
+    int e = ex - 1;           /* a = (2m) * 2^e, 1 <= 2m < 2 */
+    if (e < -14) {
+        /* subnormal range: multiples of 2^-24; rint rounds to nearest, ties to even */
+        double q = rint(ldexp(a, 24));
+        return (uint16_t)(sign | (uint16_t)q); /* q == 1024 is the smallest normal number */
+    }
+    double q = rint(ldexp(2.0 * m - 1.0, 10)); /* fraction in units of 2^-10, 0 .. 1024 */
+    if (q == 1024.0) {
+        q = 0.0;
+        e += 1;
+    }
+    if (e > 15) return (uint16_t)(sign | 0x7c00u);
+    return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)q);
+}
+
+/* out[t] = binary16 pattern of in[t], t < n */
+int oracle_round_to_half(int64_t n, const double *in, uint16_t *out)
+{
+    if (n < 0 || (n > 0 && (!in || !out))) return -1;
+    for (int64_t t = 0; t < n; ++t) out[t] = oracle_double_to_half_bits(in[t]);
     return 0;
 }
 

@@ -36,7 +36,7 @@ def build(force=False):
         return _LIB
     tmp = _LIB + ".tmp%d" % os.getpid()
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-           "-ffp-contract=off", "-fno-fast-math", "-o", tmp, _SRC]
+           "-ffp-contract=off", "-fno-fast-math", "-o", tmp, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
     os.replace(tmp, _LIB)
     return _LIB
@@ -57,6 +57,10 @@ def _load():
         lib.oracle_half_bits_to_double.argtypes = [ctypes.c_uint16]
         lib.oracle_half_bits_to_double.restype = ctypes.c_double
         lib.oracle_num_threads.restype = i32
+        lib.oracle_double_to_half_bits.argtypes = [ctypes.c_double]
+        lib.oracle_double_to_half_bits.restype = ctypes.c_uint16
+        lib.oracle_round_to_half.argtypes = [i64, p, p]
+        lib.oracle_round_to_half.restype = i32
         _lib = lib
     return _lib
 
@@ -67,6 +71,21 @@ def num_threads():
 
 def half_bits_to_double(bits):
     return float(_load().oracle_half_bits_to_double(int(bits) & 0xFFFF))
+
+
+def double_to_half_bits(value):
+    """Binary16 pattern of one float64, rounded to nearest even."""
+    return int(_load().oracle_double_to_half_bits(float(value)))
+
+
+def round_to_half(values):
+    """Binary16 (numpy float16 array, same shape) of a float64 array, each element rounded once
+    to nearest even: what the binary16-output entry point stores for an exact sum."""
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    out = np.zeros(max(v.size, 1), dtype=np.uint16)
+    if _load().oracle_round_to_half(v.size, v.ctypes.data, out.ctypes.data) != 0:
+        raise ValueError("oracle_round_to_half rejected its arguments")
+    return out[:v.size].view(np.float16).reshape(v.shape)
 
 
 def _packed_ld(layout, rows, cols):

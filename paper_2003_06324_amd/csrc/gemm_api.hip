@@ -26,9 +26,11 @@ GEMM_DECLARE_TILE(float, 64, 64, 2, 2)
 
 namespace {
 
-// Sums the K-slices of the workspace in slice order (deterministic) into C.
+// Sums the K-slices of the workspace in slice order (deterministic) into C; TC is float, or
+// _Float16 for the binary16-output entry point (one rounding, to nearest even, of the sum).
+template <typename TC>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int64_t split_stride,
-                                                            int splits, float *C, int64_t ldc,
+                                                            int splits, TC *C, int64_t ldc,
                                                             int M, int N)
 {
     const int64_t total = (int64_t)M * N;
@@ -37,17 +39,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int
         float s = 0.0f;
         for (int z = 0; z < splits; ++z) s += ws[z * split_stride + idx];
         const int64_t r = idx / N, c = idx - r * N;
-        C[r * ldc + c] = s;
+        C[r * ldc + c] = (TC)s;
     }
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(float *C, int64_t ldc, int M, int N)
+template <typename TC>
+__global__ __launch_bounds__(256) void fill_zero_kernel(TC *C, int64_t ldc, int M, int N)
 {
     const int64_t total = (int64_t)M * N;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * 256) {
         const int64_t r = idx / N, c = idx - r * N;
-        C[r * ldc + c] = 0.0f;
+        C[r * ldc + c] = (TC)0.0f;
     }
 }
 
@@ -173,11 +176,13 @@ int get_workspace(size_t bytes, void **out)
     return GEMM_OK;
 }
 
-template <typename T>
+// T: operand type; TC: element type of C (float, or _Float16 for gemm_f16f16)
+template <typename T, typename TC>
 int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t lda,
-              const void *B, int layB, int64_t ldb, float *C, int layC, int64_t ldc, void *stream_)
+              const void *B, int layB, int64_t ldb, TC *C, int layC, int64_t ldc, void *stream_)
 {
     constexpr bool f32 = sizeof(T) == 4;
+    constexpr bool out16 = sizeof(TC) == 2;
     constexpr int64_t kMax = 2147483647LL - 256;
     if (M < 0 || N < 0 || K < 0) return GEMM_ERR_INVALID_ARG;
     if (lda < 0 || ldb < 0 || ldc < 0) return GEMM_ERR_INVALID_ARG;
@@ -205,7 +210,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     if (K == 0) {
         const int64_t total = M * N;
         const int blocks = (int)(cdiv(total, 256) < 65536 ? cdiv(total, 256) : 65536);
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, C, ldc, (int)M, (int)N);
+        hipLaunchKernelGGL(fill_zero_kernel<TC>, dim3(blocks), dim3(256), 0, stream, C, ldc, (int)M, (int)N);
         if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
         snprintf(t_last_config, sizeof t_last_config, "%s zero-fill", f32 ? "f32" : "f16");
         return GEMM_OK;
@@ -247,6 +252,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.kt_per_split = (int)kt_per_split;
     a.splits = splits;
     a.ld32 = ld32 ? 1 : 0;
+    a.out16 = 0;
     void *ws = nullptr;
     if (splits > 1) {
         const int rc = get_workspace((size_t)splits * (size_t)M * (size_t)N * sizeof(float), &ws);
@@ -255,9 +261,10 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         a.ldc = N;
         a.split_stride = M * N;
     } else {
-        a.C = C;
+        a.C = (float *)C;
         a.ldc = ldc;
         a.split_stride = 0;
+        a.out16 = out16 ? 1 : 0;
     }
     const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n * splits, 8)));
     const launch_fn fn = f32 ? t.f32 : t.f16;
@@ -270,11 +277,11 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     if (splits > 1) {
         const int64_t total = M * N;
         const int blocks = (int)(cdiv(total, 256) < 4096 ? cdiv(total, 256) : 4096);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, (const float *)ws,
+        hipLaunchKernelGGL(splitk_reduce_kernel<TC>, dim3(blocks), dim3(256), 0, stream, (const float *)ws,
                            (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
         if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
     }
-    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d", f32 ? "f32" : "f16", t.name,
+    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d", f32 ? "f32" : (out16 ? "f16f16" : "f16"), t.name,
              akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits);
     return GEMM_OK;
 }
@@ -286,14 +293,22 @@ extern "C" {
 int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int layoutA, int64_t lda,
              const float *B, int layoutB, int64_t ldb, float *C, int layoutC, int64_t ldc, void *hip_stream)
 {
-    return gemm_impl<float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
+    return gemm_impl<float, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
 }
 
 int gemm_f16f32(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA, int64_t lda,
                 const uint16_t *B, int layoutB, int64_t ldb, float *C, int layoutC, int64_t ldc,
                 void *hip_stream)
 {
-    return gemm_impl<_Float16>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
+    return gemm_impl<_Float16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
+}
+
+int gemm_f16f16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA, int64_t lda,
+                const uint16_t *B, int layoutB, int64_t ldb, uint16_t *C, int layoutC, int64_t ldc,
+                void *hip_stream)
+{
+    return gemm_impl<_Float16, _Float16>(M, N, K, A, layoutA, lda, B, layoutB, ldb, (_Float16 *)C, layoutC, ldc,
+                                         hip_stream);
 }
 
 int gemm_force_config(const char *name)

@@ -58,7 +58,7 @@ constexpr int NSLOT = 5;          // operand slots in the LDS ring of the direct
 struct KernelArgs {
     const void *A;       // M x K
     const void *B;       // K x N
-    float *C;            // row-major M x N, or the split-K workspace
+    float *C;            // row-major M x N (binary16 elements if out16), or the split-K workspace
     int64_t lda, ldb, ldc;
     int64_t split_stride;  // elements between consecutive K-slices of the workspace
     int M, N, K;
@@ -66,6 +66,7 @@ struct KernelArgs {
     int kt_per_split;    // slabs per K-slice
     int splits;          // number of K-slices; the grid holds tiles_m * tiles_n * splits work items
     int ld32;            // 256 * ld * sizeof(element) < 2^31 for A and B: tile-local byte offsets fit 32 bits
+    int out16;           // C holds binary16: the accumulators are rounded (to nearest even) at the store
 };
 
 template <typename T> struct Elem;
@@ -796,6 +797,49 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     // epilogue: accumulator register r of lane l holds
     //   row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 block
     float *C = p.C + (int64_t)slice * p.split_stride;
+    if (p.out16) {
+        // binary16 result (never combined with K-slices: those reduce from binary32 partials)
+        _Float16 *Ch = (_Float16 *)p.C;
+#if defined(__HIP_DEVICE_COMPILE__)
+        if (p.ldc < (int64_t(1) << 20)) {
+            // same range-checked descriptor as the binary32 edge-tile stores below
+            const int ldc2 = (int)p.ldc * 2;
+            const int rows_valid = p.M - m0 < BM ? p.M - m0 : BM;
+            const __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc((void *)(Ch + (int64_t)m0 * p.ldc + n0), 0, rows_valid * ldc2, 0x00020000);
+            const int voff = (wm * TM + 4 * (lane >> 5)) * ldc2 + (wn * TN + (lane & 31)) * 2;
+            int voffj[FN];
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                voffj[j] = n0 + wn * TN + j * 32 + (lane & 31) < p.N ? voff + j * 64 : (int)0x80000000;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int roff = (i * 32 + 8 * (r >> 2) + (r & 3)) * ldc2;
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        const _Float16 h = (_Float16)acc[i][j][r];
+                        __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, h), rsrc, voffj[j] + roff, 0, 0);
+                    }
+                }
+            return;
+        }
+#endif
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn * TN + j * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (row < p.M && col < p.N) Ch[(int64_t)row * p.ldc + col] = (_Float16)acc[i][j][r];
+                }
+            }
+        }
+        return;
+    }
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc does not know the buffer builtins
     // Tiles that lie fully inside C (and whose byte offsets fit 32 bits) store through a
     // buffer descriptor based at the tile origin: the per-lane part of the address is one

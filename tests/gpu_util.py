@@ -22,8 +22,9 @@ def to_device(buf):
 
 
 def run_gpu(dtype, A, B, la, lb, lc=gi.ROW_MAJOR, pads=(0, 0, 0), offsets=(0, 0, 0), force=None,
-            return_config=False):
-    """HIP path on logical matrices A (M x K), B (K x N); returns logical float32 C.
+            return_config=False, out="f32"):
+    """HIP path on logical matrices A (M x K), B (K x N); returns logical float32 C
+    (out="f16": the binary16-output entry point, returns a float16 array).
 
     pads: extra leading-dimension elements per operand (padding is NaN-filled and, for C,
     checked to be untouched).  offsets: element offsets of each base pointer inside its
@@ -42,13 +43,14 @@ def run_gpu(dtype, A, B, la, lb, lc=gi.ROW_MAJOR, pads=(0, 0, 0), offsets=(0, 0,
     c_major = M if lc == gi.ROW_MAJOR else N
     c_minor = N if lc == gi.ROW_MAJOR else M
     c_len = ((c_major - 1) * ldc + c_minor) if (M > 0 and N > 0) else 0
-    dC = torch.full((offsets[2] + c_len + 8,), float("nan"), dtype=torch.float32, device="cuda")
-    fn = g.gemm_f32 if dtype == "f32" else g.gemm_f16f32
+    c_np, c_torch, c_esz = (np.float32, torch.float32, 4) if out == "f32" else (np.float16, torch.float16, 2)
+    dC = torch.full((offsets[2] + c_len + 8,), float("nan"), dtype=c_torch, device="cuda")
+    fn = g.gemm_f32 if dtype == "f32" else (g.gemm_f16f32 if out == "f32" else g.gemm_f16f16)
     stream = torch.cuda.current_stream().cuda_stream
     g.force_config(force)
     try:
         fn(M, N, K, dA.data_ptr() + offsets[0] * esz, la, lda, dB.data_ptr() + offsets[1] * esz, lb, ldb,
-           dC.data_ptr() + offsets[2] * 4, lc, ldc, stream)
+           dC.data_ptr() + offsets[2] * c_esz, lc, ldc, stream)
         cfg = g.last_config()
     finally:
         g.force_config(None)
@@ -58,7 +60,7 @@ def run_gpu(dtype, A, B, la, lb, lc=gi.ROW_MAJOR, pads=(0, 0, 0), offsets=(0, 0,
         "wrote outside C"
     body = host[offsets[2]:offsets[2] + c_len]
     if c_len and pads[2]:
-        full = np.full(c_major * ldc, np.nan, np.float32)
+        full = np.full(c_major * ldc, np.nan, c_np)
         full[:c_len] = body
         assert np.all(np.isnan(full.reshape(c_major, ldc)[:, c_minor:].reshape(-1)[:-pads[2]])), \
             "wrote into the ld padding of C"

@@ -163,6 +163,50 @@ def test_half_decode_all_bit_patterns(oracle):
     assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
 
 
+def test_half_rounding_hand_constants(oracle):
+    path = os.path.join(os.path.dirname(__file__), "golden", "binary16_rounding_constants.txt")
+    n = 0
+    for line in open(path):
+        fields = line.split("#")[0].split()
+        if not fields:
+            continue
+        value = float.fromhex(fields[0]) if "p" in fields[0] else float(fields[0])
+        assert oracle.double_to_half_bits(value) == int(fields[1], 16), fields
+        n += 1
+    assert n >= 20
+
+
+def test_half_rounding_round_trip_and_ties(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    vals = bits.view(np.float16).astype(np.float64)
+    finite = np.isfinite(vals)
+    # every binary16 value encodes back to its own pattern (infinities included)
+    back = oracle.round_to_half(vals[~np.isnan(vals)]).view(np.uint16)
+    assert np.array_equal(back, bits[~np.isnan(vals)])
+    assert np.all(np.isnan(oracle.round_to_half(vals[np.isnan(vals)]).astype(np.float64)))
+    # the exact midpoint of two neighbours goes to the one with the even pattern; a hair to
+    # either side goes to the nearer one (positive finite patterns h, h+1)
+    h = np.arange(0, 0x7BFF, dtype=np.uint16)
+    lo, hi = vals[h], vals[h + 1]
+    assert np.all(finite[h] & finite[h + 1])
+    mid = (lo + hi) / 2          # exact in float64: 11 + 1 significant bits
+    even = np.where(h % 2 == 0, h, h + 1)
+    assert np.array_equal(oracle.round_to_half(mid).view(np.uint16), even)
+    assert np.array_equal(oracle.round_to_half(-mid).view(np.uint16), even | 0x8000)
+    eps = (hi - lo) * 2.0 ** -20
+    assert np.array_equal(oracle.round_to_half(mid - eps).view(np.uint16), h)
+    assert np.array_equal(oracle.round_to_half(mid + eps).view(np.uint16), h + 1)
+
+
+def test_half_rounding_matches_numpy_conversion(oracle):
+    # numpy's float64 -> float16 cast is an independent implementation of the same rounding
+    rng = np.random.default_rng(42)
+    x = rng.standard_normal(200000) * np.exp(rng.uniform(-20.0, 11.0, 200000))
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.round_to_half(x).view(np.uint16), want)
+
+
 def test_half_subnormals_and_extremes_in_product(oracle):
     # smallest subnormal times largest normal; exact in float64
     A = np.array([[0x0001, 0x7BFF, 0x8001]], np.uint16).view(np.float16)
