@@ -22,11 +22,12 @@
 // 16 lanes at a time and a b64 read 32 lanes at a time, so the swizzles are
 // chosen to spread every such lane group over all 64 banks.
 //
-// Both images are produced either by direct 16-byte global->LDS loads (each
-// wave fills 1 KiB of LDS per instruction, lane l writing bytes [16l, 16l+16),
-// so the swizzle is applied by choosing which global granule a lane fetches)
-// or, for ragged K tails and unaligned operands, by guarded element loads
-// through registers that write the same positions.
+// Both images are produced by direct 16-byte global->LDS loads (each wave fills
+// 1 KiB of LDS per instruction, lane l writing bytes [16l, 16l+16), so the
+// swizzle is applied by choosing which global granule a lane fetches); for
+// operands that are not 16-byte aligned by the same granules fetched through
+// registers and written to the same positions; and for ragged K tails by
+// guarded loads through registers.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -36,16 +37,13 @@ namespace gemm_gfx950 {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef __fp16 fp16x4_t __attribute__((__vector_size__(4 * sizeof(__fp16))));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
-typedef int int2_t __attribute__((ext_vector_type(2)));
 typedef int int4_t __attribute__((ext_vector_type(4)));
 
 #define GEMM_LDS(T) __attribute__((address_space(3))) T
-#define GEMM_GLB(T) __attribute__((address_space(1))) T
 
 #ifndef GEMM_KGS
 #define GEMM_KGS 4
@@ -415,11 +413,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     constexpr int SLOT = A_BYTES > B_BYTES ? A_BYTES : B_BYTES;  // one operand slab
     constexpr int NBUF = ALIGNED ? NSLOT : 4;  // ring of five operand slots, or two buffers of (A, B)
     typedef typename Frag<T>::type frag_t;
-    // LDS reads and MFMAs per k-group (for the interleave hints)
-    constexpr int RD_A = sizeof(T) == 2 ? (AKC ? 1 : 2) : (AKC ? 1 : 4);
-    constexpr int RD_B = sizeof(T) == 2 ? (BKC ? 1 : 2) : (BKC ? 1 : 4);
-    constexpr int NDS = FM * RD_A + FN * RD_B;
-    constexpr int NMMA = FM * FN * (sizeof(T) == 2 ? 1 : 4);
     constexpr int NVA = A_BYTES / 1024 / NW;  // direct loads per wave per A slab
     constexpr int NVB = B_BYTES / 1024 / NW;
     static_assert(KGS == 4, "the pipeline below is written for four k-groups per slab");
@@ -534,18 +527,19 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         }
     };
     if (ALIGNED) {
-        // Full slabs: direct global->LDS loads into a ring of NSLOT = 5 operand slots.
-        // Operand slabs are fetched in the order A(0) B(0) A(1) B(1) ..., slab number h going
-        // to slot h % 5, so tile t has A in slot 2t % 5 and B in the next one, and one slot
-        // is always spare.  Per tile t (four k-groups, operand registers double-buffered):
-        //   k-groups 0,1: MFMAs; fetch operands of the next k-group; issue A(t+2) into
+        // Full slabs: direct global->LDS loads into a ring of NSLOT = 5 operand slots.  One
+        // operand, called X below, goes first: slabs are fetched in the order X(0) Y(0) X(1)
+        // Y(1) ..., slab number h going to slot h % 5, so tile t has X in slot 2t % 5 and Y
+        // in the next one, and one slot is always spare.  Per tile t (four k-groups, operand
+        // registers double-buffered):
+        //   k-groups 0,1: MFMAs; fetch operands of the next k-group; issue X(t+2) into
         //                 the spare slot, half of its loads per k-group;
         //   k-group 2:    MFMAs; fetch operands of k-group 3;
-        //   counted wait: everything but A(t+2) has landed, i.e. tile t+1 is complete;
+        //   counted wait: everything but X(t+2) has landed, i.e. tile t+1 is complete;
         //   barrier:      every wave holds k-group 3 in registers, tile t's slots are free;
-        //   k-group 3:    MFMAs; issue B(t+2) into A(t)'s slot; fetch k-group 0 of tile t+1.
-        // So loads are in flight all the time (32..96 KiB of the 160 KiB LDS), A slabs have
-        // two tiles of MFMA time to land and B slabs one.  Past the end of K the loaders
+        //   k-group 3:    MFMAs; issue Y(t+2) into X(t)'s slot; fetch k-group 0 of tile t+1.
+        // So loads are in flight all the time (32..96 KiB of the 160 KiB LDS), X slabs have
+        // two tiles of MFMA time to land and Y slabs one.  Past the end of K the loaders
         // re-fetch the last slab (never read), which keeps the loop body branch-free and
         // the number of outstanding loads constant for the counted waits.
         const int n = (kend - k_done) / BK;
