@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the zero-data and binary16-output context runs (they launch the headline kernels "
+                         "on other data, which would mix into per-kernel averages of a profiler)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is single-GPU (a GEMM tile needs no exchange; see DESIGN.md); run with --gpus 1")
@@ -140,26 +143,28 @@ def main():
                 "kernel": per_layout[dom]["kernel"], "flop_per_launch": flop,
                 "avg_launch_ms": per_layout[dom]["ms"]}
 
-    # --- context, not part of the timed step: the same four launches on all-zero operands.  With
-    # N(0,1) data the part lowers its clock to stay inside its power limit; zeros do not toggle the
-    # matrix cores' inputs, so this is the rate of the same kernels at (nearly) the full clock.
-    Z = torch.zeros(S * S, dtype=torch.int16, device="cuda")
-    CZ = torch.empty(S * S, dtype=torch.float32, device="cuda")  # the headline results stay untouched
-    zcalls = [c[:3] + (Z, c[4], 0, Z, c[7], 0, CZ) + c[10:] for c in calls]
-    zwall, _ = time_calls(g.gemm_f16f32, zcalls, max(5, args.steps // 5), max(2, args.warmup // 5))
-    z_tflops = 4 * flop / (zwall / max(5, args.steps // 5)) / 1e12
-    zero_data = {"workload": "same four launches, all-zero operands (no data-dependent clock throttling)",
-                 "tflops": round(z_tflops, 1), "frac_of_peak": round(z_tflops / PEAK_TFLOPS["f16"], 4)}
-    del Z, CZ
+    zero_data = fp16_out = None
+    if not args.no_context:
+        # --- context, not part of the timed step: the same four launches on all-zero operands.  With
+        # N(0,1) data the part lowers its clock to stay inside its power limit; zeros do not toggle the
+        # matrix cores' inputs, so this is the rate of the same kernels at (nearly) the full clock.
+        Z = torch.zeros(S * S, dtype=torch.int16, device="cuda")
+        CZ = torch.empty(S * S, dtype=torch.float32, device="cuda")  # the headline results stay untouched
+        zcalls = [c[:3] + (Z, c[4], 0, Z, c[7], 0, CZ) + c[10:] for c in calls]
+        zwall, _ = time_calls(g.gemm_f16f32, zcalls, max(5, args.steps // 5), max(2, args.warmup // 5))
+        z_tflops = 4 * flop / (zwall / max(5, args.steps // 5)) / 1e12
+        zero_data = {"workload": "same four launches, all-zero operands (no data-dependent clock throttling)",
+                     "tflops": round(z_tflops, 1), "frac_of_peak": round(z_tflops / PEAK_TFLOPS["f16"], 4)}
+        del Z, CZ
 
-    # --- context: the binary16-output entry point on the NT case (the operand and result types of
-    # the paper's own tensor-core kernels and of the half-precision routine it is measured against)
-    C16 = torch.empty(S * S, dtype=torch.float16, device="cuda")
-    nt = calls[names.index("NT")]
-    _, pc16 = time_calls(g.gemm_f16f16, [nt[:9] + (C16,) + nt[10:]], max(5, args.steps // 2), max(2, args.warmup // 2))
-    fp16_out = {"workload": "f16f16_%dx%dx%d_NT (binary16 C)" % (S, S, S), "ms": round(pc16[0], 4),
-                "tflops": round(flop / pc16[0] / 1e9, 1), "kernel": g.last_config()}
-    del C16
+        # --- context: the binary16-output entry point on the NT case (the operand and result types of
+        # the paper's own tensor-core kernels and of the half-precision routine it is measured against)
+        C16 = torch.empty(S * S, dtype=torch.float16, device="cuda")
+        nt = calls[names.index("NT")]
+        _, pc16 = time_calls(g.gemm_f16f16, [nt[:9] + (C16,) + nt[10:]], max(5, args.steps // 2), max(2, args.warmup // 2))
+        fp16_out = {"workload": "f16f16_%dx%dx%d_NT (binary16 C)" % (S, S, S), "ms": round(pc16[0], 4),
+                    "tflops": round(flop / pc16[0] / 1e9, 1), "kernel": g.last_config()}
+        del C16
 
     # --- secondary workload (not part of the timed step): FP32 4096^3, A row-major, B column-major
     A32_np, B32_np = gi.make_problem(2000, 4096, 4096, 4096, "uniform", "f32")
@@ -182,8 +187,10 @@ def main():
         "config": {"workload": "f16f32_%dx%dx%d_NN+NT+TN+TT" % (S, S, S), "gemms_per_step": 4,
                    "entries": "N(0,1) rounded to binary16, seed 3000", "C": "binary32 row-major"},
         "pct_of_peak": round(100.0 * value / PEAK_TFLOPS["f16"], 2),
-        "per_layout": per_layout, "roofline": roofline, "zero_data": zero_data, "fp16_out": fp16_out, "fp32": fp32,
+        "per_layout": per_layout, "roofline": roofline, "fp32": fp32,
     }
+    if zero_data is not None:
+        out["zero_data"], out["fp16_out"] = zero_data, fp16_out
     if not args.no_cpu_baseline:
         def gpu_rows(rows):
             return outs["NT"][: rows * S].cpu().numpy().reshape(rows, S)
