@@ -3,6 +3,13 @@ optionally, a plain device-to-device copy of known size whose FETCH_SIZE / WRITE
 readings calibrate the HBM-traffic counters.
 
     python3 -m paper_2003_06324_amd.profile_workload --dtype f16 --size 8192 --layout NT --iters 5 --copy-mib 1024
+
+With --sustain SECONDS it instead keeps the launches going for that long while a thread samples
+`amd-smi metric -p -c` (socket power, per-XCD clocks) and prints rate, power, clock and energy
+per launch: the part holds a power limit by lowering its clock, which is what bounds the
+random-data figures.
+
+    python3 -m paper_2003_06324_amd.profile_workload --size 8192 --layout NT --dist normal --sustain 4
 """
 import argparse
 import os
@@ -20,6 +27,7 @@ def main():
     ap.add_argument("--iters", type=int, default=5)
     ap.add_argument("--copy-mib", type=int, default=0, help="also run a copy kernel of this many MiB")
     ap.add_argument("--force", default=None, help="tile configuration override, e.g. t256x256")
+    ap.add_argument("--sustain", type=float, default=0.0, help="seconds of back-to-back launches with power sampling")
     args = ap.parse_args()
 
     import torch
@@ -43,6 +51,11 @@ def main():
     fn = g.gemm_f16f32 if args.dtype == "f16" else g.gemm_f32
     stream = torch.cuda.current_stream().cuda_stream
     g.force_config(args.force)
+    if args.sustain > 0:
+        sustain(lambda: fn(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream), args.sustain,
+                2.0 * M * N * K, "%s %dx%dx%d %s %s" % (args.dtype, M, N, K, args.layout, args.dist))
+        print("gemm:", g.last_config())
+        return
     for _ in range(args.iters):
         fn(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
     torch.cuda.synchronize()
@@ -55,6 +68,52 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print("copy: %d MiB read + %d MiB written, x3" % (args.copy_mib, args.copy_mib))
+
+
+def sustain(launch, seconds, flop, what):
+    import json
+    import subprocess
+    import threading
+    import time
+    import torch
+    samples, stop = [], []
+
+    def sampler():
+        while not stop:
+            try:
+                out = subprocess.run(["amd-smi", "metric", "-p", "-c", "--json"], capture_output=True, text=True,
+                                     timeout=10).stdout
+                gpu = json.loads(out)["gpu_data"][0]
+                clocks = [v["clk"]["value"] for k, v in gpu["clock"].items() if k.startswith("gfx_")]
+                samples.append((float(gpu["power"]["socket_power"]["value"]), sum(clocks) / len(clocks)))
+            except Exception:
+                pass
+            time.sleep(0.3)
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    for _ in range(10):
+        launch()
+    torch.cuda.synchronize()
+    t0, n = time.time(), 0
+    while time.time() - t0 < seconds:
+        for _ in range(50):
+            launch()
+        torch.cuda.synchronize()
+        n += 50
+    dt = time.time() - t0
+    stop.append(1)
+    th.join()
+    steady = samples[len(samples) // 3:] or samples
+    line = "%s: %.1f TFLOP/s, %.1f us per launch" % (what, flop * n / dt / 1e12, dt / n * 1e6)
+    if steady:
+        watts = sum(s[0] for s in steady) / len(steady)
+        mhz = sum(s[1] for s in steady) / len(steady)
+        line += ", socket power %.0f W, mean XCD clock %.0f MHz, %.0f mJ per launch (%d samples)" % (
+            watts, mhz, watts * dt / n * 1e3, len(steady))
+    else:
+        line += ", no power samples (amd-smi not usable here)"
+    print(line, flush=True)
 
 
 if __name__ == "__main__":
