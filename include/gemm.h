@@ -109,6 +109,16 @@ int gemm_f16f16(int64_t M, int64_t N, int64_t K,
  */
 int gemm_force_config(const char *name);
 
+/*
+ * The configuration the selection would pick (or the forced one), without touching the
+ * device: elem_bytes is 2 (binary16 operands) or 4 (binary32); aligned != 0 means both
+ * operands qualify for the direct-load kernels (16-byte aligned bases and leading
+ * dimensions).  Writes "<tile>:s<splits>" into buf (NUL-terminated, truncated to buflen).
+ * This is the host side of the per-size tuning of Section 5.3, exposed so that it can be
+ * tested without a GPU.
+ */
+int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen);
+
 /* Number of tile configurations, and the name of the i-th (NULL if out of range). */
 int gemm_num_configs(void);
 const char *gemm_config_name(int i);

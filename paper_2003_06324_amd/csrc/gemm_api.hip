@@ -311,6 +311,24 @@ int gemm_f16f16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA,
                                          hip_stream);
 }
 
+int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen)
+{
+    if ((elem_bytes != 2 && elem_bytes != 4) || M <= 0 || N <= 0 || K <= 0 || !buf || buflen <= 0)
+        return GEMM_ERR_INVALID_ARG;
+    const bool f32 = elem_bytes == 4;
+    const int64_t BK = f32 ? Elem<float>::BK : Elem<_Float16>::BK;
+    const int64_t KT = cdiv(K, BK);
+    int tile, splits;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        choose(M, N, K, KT, f32, aligned != 0, tile, splits);
+    }
+    const int64_t per = cdiv(KT, splits);
+    splits = (int)cdiv(KT, per);  // no empty slices, as in the launch path
+    snprintf(buf, (size_t)buflen, "%s:s%d", kTiles[tile].name, splits);
+    return GEMM_OK;
+}
+
 int gemm_force_config(const char *name)
 {
     std::lock_guard<std::mutex> lock(g_mutex);

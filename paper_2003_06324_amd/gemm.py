@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_force_config", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -52,6 +52,8 @@ def load_library():
         fn.restype = i32
     lib.gemm_force_config.argtypes = [ctypes.c_char_p]
     lib.gemm_force_config.restype = i32
+    lib.gemm_query_config.argtypes = [i32, i64, i64, i64, i32, ctypes.c_char_p, i32]
+    lib.gemm_query_config.restype = i32
     lib.gemm_num_configs.argtypes = []
     lib.gemm_num_configs.restype = i32
     lib.gemm_config_name.argtypes = [i32]
@@ -103,6 +105,13 @@ def gemm_f16f16(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stre
     rc = load_library().gemm_f16f16(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
                                     _ptr(C), layoutC, ldc, stream or None)
     return _check(rc) if check else rc
+
+
+def query_config(elem_bytes, M, N, K, aligned=True):
+    """The "<tile>:s<splits>" the selection picks for this shape (host only, nothing is launched)."""
+    buf = ctypes.create_string_buffer(64)
+    _check(load_library().gemm_query_config(elem_bytes, M, N, K, 1 if aligned else 0, buf, 64))
+    return buf.value.decode()
 
 
 def force_config(name=None, check=True):

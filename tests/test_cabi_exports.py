@@ -40,3 +40,43 @@ def test_host_only_entry_points():
     assert g.gemm_f32(2, 2, 2, None, 0, 0, 16, 0, 0, 16, 0, 0, check=False) == -1
     assert g.gemm_f32(2 ** 31, 1, 1, 16, 0, 0, 16, 0, 0, 16, 0, 0, check=False) == -3
     assert g.gemm_f32(0, 0, 5, None, 0, 0, None, 0, 0, None, 0, 0) == 0
+
+
+def test_selection_of_tile_and_k_slices():
+    """Host side of the per-size tuning (paper Section 5.3): big products get the biggest tile
+    and no K slices; few tiles with a deep K get slices; tiny products the small tile; operands
+    that are not 16-byte aligned the 8-wave tile.  The expected picks are the ones the sweep
+    under profiles/ found to be the fastest forced configuration on the part."""
+    import paper_2003_06324_amd as g
+    g.force_config(None)
+    q = g.query_config
+    assert q(2, 8192, 8192, 8192) == "t256x256:s1"
+    assert q(2, 4096, 4096, 4096) == "t256x256:s1"
+    assert q(2, 2048, 2048, 2048) == "t128x128:s1"
+    assert q(2, 1024, 1024, 1024) == "t64x64:s1"
+    assert q(2, 256, 256, 256) == "t64x64:s1"
+    assert q(2, 1024, 1024, 65536) == "t256x256:s16"
+    assert q(2, 8192, 128, 8192) == "t128x128:s4"
+    assert q(2, 128, 8192, 8192) == "t128x128:s4"
+    assert q(2, 4097, 3073, 1025, aligned=False) == "t256x256w8:s1"
+    assert q(2, 1000, 1500, 2000, aligned=False) == "t64x64:s1"
+    assert q(4, 4096, 4096, 4096) == "t256x256:s1"
+    assert q(4, 256, 256, 256) == "t64x64:s1"
+    # never more slices than K slabs (64 k for binary16, 32 k for binary32), none without K to spare
+    for K in (1, 63, 64, 65, 200, 1000):
+        tile, s = q(2, 64, 64, K).split(":s")
+        assert 1 <= int(s) <= -(-K // 64)
+        tile, s = q(4, 64, 64, K).split(":s")
+        assert 1 <= int(s) <= -(-K // 32)
+    # a deeper K never gets fewer slices on a shape with few tiles
+    last = 1
+    for K in (1024, 4096, 16384, 65536, 262144):
+        s = int(q(2, 512, 512, K).split(":s")[1])
+        assert s >= last
+        last = s
+    # forcing overrides the selection, slice count clipped to the slabs there are
+    g.force_config("t128x128:s8")
+    assert q(2, 8192, 8192, 8192) == "t128x128:s8"
+    assert q(2, 8192, 8192, 130) == "t128x128:s3"
+    g.force_config(None)
+    assert g.load_library().gemm_query_config(3, 1, 1, 1, 1, None, 0) == -1
