@@ -129,3 +129,62 @@ def test_paper_sizes(oracle, case):
     Ai, Bi = gi.make_problem(601 + M + N + K, M, N, K, "int", dtype)
     refi = oracle.gemm(M, N, K, Ai, 0, Bi, 0, dtype).astype(np.float32)
     assert np.array_equal(run_gpu(dtype, Ai, Bi, la, lb), refi), case
+
+
+def test_c_beyond_4_gib(oracle):
+    # C of 33000 x 33000 binary32 is 4.36 GB: row offsets into C cross 2^32 bytes.  Integer-valued
+    # operands, so sampled entries (also in the last rows) must match the oracle exactly.
+    import torch
+    import paper_2003_06324_amd as g
+    M = N = 33000
+    K = 64
+    A, B = gi.make_problem(61, M, N, K, "int", "f16")
+    dA = torch.from_numpy(A.view(np.int16)).cuda()
+    dB = torch.from_numpy(np.ascontiguousarray(B.T).view(np.int16)).cuda()
+    dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+    g.gemm_f16f32(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0,
+                  torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    rows, cols = sample_positions(M, N, 4000, 3)
+    ref = oracle.gemm_at(M, N, K, gi.store(A, gi.ROW_MAJOR), gi.ROW_MAJOR, 0,
+                         gi.store(B, gi.COL_MAJOR), gi.COL_MAJOR, 0, rows, cols, "f16")
+    idx = torch.from_numpy(rows * N + cols).cuda()
+    got = dC[idx].cpu().numpy()
+    assert np.array_equal(got, ref.astype(np.float32))
+    # every row and column sum of the whole of C, exact in int64 (sums of |C| stay far below 2^53)
+    Ai, Bi = A.astype(np.int64), B.astype(np.int64)
+    C2 = dC.view(M, N)
+    assert np.array_equal(C2.sum(dim=1, dtype=torch.float64).cpu().numpy(), (Ai @ Bi.sum(axis=1)).astype(np.float64))
+    assert np.array_equal(C2.sum(dim=0, dtype=torch.float64).cpu().numpy(), (Ai.sum(axis=0) @ Bi).astype(np.float64))
+
+
+def test_operand_beyond_4_gib(oracle):
+    # A of 66000 x 32768 binary16 is 4.33 GB: tile origins in A lie beyond 2^32 bytes
+    # (a formula instead of the seeded generator keeps the host side to a few seconds)
+    import torch
+    import paper_2003_06324_amd as g
+    M, N, K = 66000, 72, 32768
+    i = np.arange(M, dtype=np.int32)[:, None]
+    k = np.arange(K, dtype=np.int32)[None, :]
+    A = (((i * 7 + k * 3) % 9) - 4).astype(np.float16)
+    B = ((np.arange(K)[:, None] * 5 + np.arange(N)[None, :] * 11) % 7 - 3).astype(np.float16)
+    dA = torch.from_numpy(A.view(np.int16)).cuda()
+    dB = torch.from_numpy(np.ascontiguousarray(B.T).view(np.int16)).cuda()
+    rows, cols = sample_positions(M, N, 1500, 4)
+    ref = oracle.gemm_at(M, N, K, A.reshape(-1), gi.ROW_MAJOR, 0, gi.store(B, gi.COL_MAJOR), gi.COL_MAJOR, 0,
+                         rows, cols, "f16").astype(np.float32)
+    stream = torch.cuda.current_stream().cuda_stream
+    for force in (None, "t256x256:s1", "t64x64:s2"):
+        dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+        g.force_config(force)
+        try:
+            g.gemm_f16f32(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, stream)
+            cfg = g.last_config()
+        finally:
+            g.force_config(None)
+        torch.cuda.synchronize()
+        C = dC.cpu().numpy().reshape(M, N)
+        assert np.array_equal(C[rows, cols], ref), cfg
+        # exact column sums of the whole of C in int64
+        col_sums = A.sum(axis=0, dtype=np.float64).astype(np.int64) @ B.astype(np.int64)   # |sums| < 2^53: exact
+        assert np.array_equal(C.sum(axis=0, dtype=np.float64), col_sums.astype(np.float64)), cfg
