@@ -253,6 +253,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.splits = splits;
     a.ld32 = ld32 ? 1 : 0;
     a.out16 = 0;
+    a.stream_c = 0;
     void *ws = nullptr;
     if (splits > 1) {
         const int rc = get_workspace((size_t)splits * (size_t)M * (size_t)N * sizeof(float), &ws);
@@ -265,6 +266,12 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         a.ldc = ldc;
         a.split_stride = 0;
         a.out16 = out16 ? 1 : 0;
+        // Non-temporal C stores (whole 128-byte lines only): measured 1-7 % faster when later rounds
+        // of tiles are still reading A and B while C is written, or when C is small; 4-7 % slower
+        // when one round of tiles writes more than the L2s hold in a single burst at the end.
+        const bool lines = !out16 && ldc % 32 == 0 && (uintptr_t)C % 128 == 0;
+        const bool rounds = tiles_m * tiles_n > (int64_t)NUM_CU * t.wg_per_cu;
+        a.stream_c = (lines && (rounds || M * N * 4 <= (32LL << 20))) ? 1 : 0;
     }
     const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n * splits, 8)));
     const launch_fn fn = f32 ? t.f32 : t.f16;
