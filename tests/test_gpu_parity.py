@@ -177,3 +177,34 @@ def test_inf_and_nan_only_where_the_inputs_put_them(oracle):
         assert np.array_equal(np.isinf(C), np.isinf(ref))
         ok = np.isfinite(ref)
         assert np.max(np.abs(C[ok] - ref[ok])) <= 2e-4 * 70
+
+
+def test_user_streams_workspace_growth_and_shutdown(oracle):
+    # Work is enqueued on the caller's stream (no priorities, plain torch streams) and ordered with
+    # what that stream already holds; the K-slice workspace grows on demand, survives being grown
+    # while earlier launches are still queued, and is rebuilt after gemm_shutdown().
+    import torch
+    import paper_2003_06324_amd as g
+    A, B = gi.make_problem(91, 192, 160, 1536, "int", "f16")
+    ref = ref_of(oracle, A, B, "f16").astype(np.float32)
+    dA = torch.from_numpy(gi.store(A, gi.ROW_MAJOR).view(np.int16)).cuda()
+    dB = torch.from_numpy(gi.store(B, gi.COL_MAJOR).view(np.int16)).cuda()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep, splits in enumerate((2, 8, 3, 16)):           # workspace 2, 8, 3, 16 slices: grows twice
+        s = streams[rep % 2]
+        with torch.cuda.stream(s):
+            dC = torch.full((192 * 160,), float("nan"), dtype=torch.float32, device="cuda")   # ordered before the GEMM
+            g.force_config("t64x64:s%d" % splits)
+            g.gemm_f16f32(192, 160, 1536, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, s.cuda_stream)
+            doubled = dC * 2.0                                                                # ordered after it
+        s.synchronize()   # one stream at a time may use the workspace (include/gemm.h)
+        outs.append((dC, doubled))
+    g.force_config(None)
+    for dC, doubled in outs:
+        assert np.array_equal(dC.cpu().numpy().reshape(192, 160), ref)
+        assert np.array_equal(doubled.cpu().numpy().reshape(192, 160), 2 * ref)
+    assert g.shutdown() == 0 and g.shutdown() == 0
+    C = run_gpu("f16", A, B, gi.ROW_MAJOR, gi.COL_MAJOR, force="t64x64:s4")
+    assert np.array_equal(C, ref)
