@@ -35,7 +35,8 @@
  * Execution
  *   Work is enqueued on hip_stream (a hipStream_t cast to void*; NULL is the
  *   default stream) of the current device.  The call does not synchronise with
- *   the host.  Shapes that are split along K use a per-device workspace that
+ *   the host.  Calls that use no K-slices only launch kernels and can be
+ *   recorded into a HIP graph; calls that do may grow the workspace first.  Shapes that are split along K use a per-device workspace that
  *   the library grows with hipMalloc on demand and frees in gemm_shutdown();
  *   calls issued concurrently on different streams of one device must not both
  *   need the workspace.

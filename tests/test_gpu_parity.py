@@ -208,3 +208,39 @@ def test_user_streams_workspace_growth_and_shutdown(oracle):
     assert g.shutdown() == 0 and g.shutdown() == 0
     C = run_gpu("f16", A, B, gi.ROW_MAJOR, gi.COL_MAJOR, force="t64x64:s4")
     assert np.array_equal(C, ref)
+
+
+def test_graph_capture_and_replay(oracle):
+    # Launches without K-slices allocate nothing, so a HIP graph can capture them.  The graph is
+    # replayed several times with eager work and synchronisation in between, and every replay is
+    # compared with the oracle (inputs change between replays, in place).
+    import torch
+    import paper_2003_06324_amd as g
+    M, N, K = 384, 320, 704
+    A0, B0 = gi.make_problem(101, M, N, K, "int", "f16")
+    dA = torch.from_numpy(gi.store(A0, gi.ROW_MAJOR).view(np.int16)).cuda()
+    dB = torch.from_numpy(gi.store(B0, gi.COL_MAJOR).view(np.int16)).cuda()
+    dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+    dC16 = torch.full((M * N,), float("nan"), dtype=torch.float16, device="cuda")
+    g.force_config("t128x128:s1")
+    try:
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            s = torch.cuda.current_stream().cuda_stream
+            g.gemm_f16f32(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, s)
+            g.gemm_f16f16(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC16, gi.ROW_MAJOR, 0, s)
+    finally:
+        g.force_config(None)
+    for rep in range(4):
+        A, B = gi.make_problem(200 + rep, M, N, K, "int", "f16")
+        dA.copy_(torch.from_numpy(gi.store(A, gi.ROW_MAJOR).view(np.int16)))
+        dB.copy_(torch.from_numpy(gi.store(B, gi.COL_MAJOR).view(np.int16)))
+        dC.fill_(float("nan"))
+        dC16.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        exact = ref_of(oracle, A, B, "f16")
+        assert np.array_equal(dC.cpu().numpy().reshape(M, N), exact.astype(np.float32)), rep
+        assert np.array_equal(dC16.cpu().numpy().reshape(M, N).view(np.uint16), oracle.round_to_half(exact).view(np.uint16)), rep
