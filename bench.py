@@ -29,7 +29,8 @@ def device_operands(A, B, layout):
 
 def time_calls(fn, calls, steps, warmup):
     """Run `calls` (list of argument tuples) per step; returns (wall seconds for `steps`
-    steps, per-call mean milliseconds from HIP events recorded on the launch stream)."""
+    steps, per-call mean milliseconds from HIP events recorded on the launch stream).
+    The clocks cannot be locked here, so median and minimum are kept beside the mean."""
     import torch
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
@@ -45,8 +46,9 @@ def time_calls(fn, calls, steps, warmup):
             events[s][i + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per_call = [sum(events[s][i].elapsed_time(events[s][i + 1]) for s in range(steps)) / steps
-                for i in range(len(calls))]
+    samples = [sorted(events[s][i].elapsed_time(events[s][i + 1]) for s in range(steps)) for i in range(len(calls))]
+    per_call = [sum(x) / steps for x in samples]
+    time_calls.spread = [(x[len(x) // 2], x[0]) for x in samples]   # (median, min) per call of the last run
     return wall, per_call
 
 
@@ -118,6 +120,7 @@ def main():
         outs[name] = C
         calls.append((S, S, S, dA, la, 0, dB, lb, 0, C, gi.ROW_MAJOR, 0))
     wall, per_call = time_calls(g.gemm_f16f32, calls, args.steps, args.warmup)
+    spread = time_calls.spread
     configs = {}
     for name, c in zip(names, calls):
         g.gemm_f16f32(*c, torch.cuda.current_stream().cuda_stream)
@@ -126,8 +129,9 @@ def main():
     flop = 2.0 * S * S * S
     ms_per_step = wall * 1e3 / args.steps
     value = 4 * flop / (ms_per_step * 1e-3) / 1e12
-    per_layout = {n: {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 1), "kernel": configs[n]}
-                  for n, ms in zip(names, per_call)}
+    per_layout = {n: {"ms": round(ms, 4), "ms_median": round(md, 4), "ms_min": round(mn, 4),
+                      "tflops": round(flop / ms / 1e9, 1), "kernel": configs[n]}
+                  for n, ms, (md, mn) in zip(names, per_call, spread)}
     # dominant kernel = the layout that takes the largest share of the step
     dom = max(names, key=lambda n: per_layout[n]["ms"])
     achieved = flop / per_layout[dom]["ms"] / 1e9

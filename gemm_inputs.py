@@ -8,8 +8,8 @@ The paper's workload is random dense matrices of a given size (Section 5
 evaluates square and rectangular sizes up to 4096 with half and single
 precision); the recipes below follow that: i.i.d. uniform[-1,1] or standard
 normal entries drawn as float32 from numpy's PCG64 generator in logical
-row-major order, rounded to binary16 (round to nearest even) for the
-half-precision cases, then stored row- or column-major per operand.  Because
+row-major order, rounded to binary16 or bfloat16 (round to nearest even) for
+the 16-bit cases, then stored row- or column-major per operand.  Because
 values are drawn in logical order, the four storage combinations of one
 (seed, shape) hold the same logical matrices.
 """
@@ -33,7 +33,26 @@ def logical_matrix(rng, rows, cols, dist, dtype):
         return x.astype(np.float16)
     if dtype == "f32":
         return x
+    if dtype == "bf16":
+        return round_to_bfloat16(x)
     raise ValueError(dtype)
+
+
+def round_to_bfloat16(x):
+    """float32 array -> float32 array whose values are bfloat16 numbers (the nearest one,
+    ties to the even pattern).  numpy has no bfloat16 type, so logical bfloat16 matrices are
+    kept as such float32 arrays and turned into 16-bit patterns by bfloat16_bits()."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return (r << 16).astype(np.uint32).view(np.float32).reshape(np.shape(x))
+
+
+def bfloat16_bits(x):
+    """uint16 patterns (the upper halves) of a float32 array holding bfloat16 values."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    if np.any(u[~np.isnan(x.reshape(u.shape))] & 0xFFFF):
+        raise ValueError("not a bfloat16 value")
+    return (u >> 16).astype(np.uint16).reshape(np.shape(x))
 
 
 def store(x, layout, ld=0):

@@ -18,8 +18,8 @@
  * The GPU path reaches this sum exactly up to rounding order, so the oracle
  * is the definition written out: one scalar float64 accumulator per output
  * element, products added in ascending k.  Operands are widened to float64
- * first; a binary16 x binary16 or binary32 x binary32 product is exact in
- * float64, so the only error is the accumulation rounding (<= K * 2^-53
+ * first; a binary16 x binary16, bfloat16 x bfloat16 or binary32 x binary32
+ * product is exact in float64, so the only error is the accumulation rounding (<= K * 2^-53
  * relative to sum |a*b|).  The result is returned as float64.
  *
  * Storage: element (r,c) of a row-major matrix with leading dimension ld sits
@@ -36,7 +36,9 @@
  * small-integer inputs against an int64 loop, closed forms, and a float64
  * numpy.matmul cross-check; for the binary16 rounding: the round trip of all
  * 65536 patterns, hand constants, exact midpoints (ties to even), the overflow
- * and subnormal thresholds, and numpy's float64 -> float16 conversion.
+ * and subnormal thresholds, and numpy's float64 -> float16 conversion; for the
+ * bfloat16 widening: all 65536 patterns against the binary32 number with the same upper
+ * half, and hand constants.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -81,6 +83,38 @@ double oracle_half_bits_to_double(uint16_t h)
         /* (1 + frac/1024) * 2^(expo-15) */
         v = 1.0 + (double)frac / 1024.0;
         int e = expo - 15;
+        while (e > 0) { v *= 2.0; --e; }
+        while (e < 0) { v *= 0.5; ++e; }
+    }
+    return sign ? -v : v;
+}
+
+/*
+ * bfloat16 bit pattern -> double, exact.  The format is the upper half of IEEE binary32:
+ * 1 sign bit, 8 exponent bits (bias 127), 7 fraction bits; normal numbers are
+ * (1 + f/128) * 2^(e-127) with 1 <= e <= 254, subnormals f * 2^-133, e == 255 is
+ * infinity (f == 0) or NaN.  Used by the bfloat16-operand sibling of the half-precision
+ * product (same specification, Section 3.1; the tensor-core instruction of Section 4.2
+ * with the other 16-bit operand format of the target).
+ */
+double oracle_bfloat16_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 7) & 0xff;
+    int frac = h & 0x7f;
+    double v;
+    if (expo == 0) {
+        v = (double)frac;
+        for (int t = 0; t < 133; ++t) v *= 0.5;
+    } else if (expo == 255) {
+        if (frac == 0) {
+            v = 1.0 / 0.0;
+        } else {
+            v = 0.0 / 0.0;
+        }
+    } else {
+        v = 1.0 + (double)frac / 128.0;
+        int e = expo - 127;
         while (e > 0) { v *= 2.0; --e; }
         while (e < 0) { v *= 0.5; ++e; }
     }
@@ -154,6 +188,31 @@ int oracle_gemm_f16(int64_t M, int64_t N, int64_t K,
     return 0;
 }
 
+int oracle_gemm_bf16(int64_t M, int64_t N, int64_t K,
+                     const uint16_t *A, int layoutA, int64_t lda,
+                     const uint16_t *B, int layoutB, int64_t ldb,
+                     double *C, int layoutC, int64_t ldc)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+    if (bad_matrix(A, layoutA, lda, M, K) || bad_matrix(B, layoutB, ldb, K, N) ||
+        bad_matrix(C, layoutC, ldc, M, N))
+        return -1;
+    if (M == 0 || N == 0) return 0;
+    double *a = (double *)malloc(sizeof(double) * (size_t)(M * K + 1));
+    double *bt = (double *)malloc(sizeof(double) * (size_t)(N * K + 1));
+    if (!a || !bt) { free(a); free(bt); return -2; }
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t k = 0; k < K; ++k)
+            a[(size_t)i * K + k] = oracle_bfloat16_bits_to_double(A[at(layoutA, lda, i, k)]);
+    for (int64_t j = 0; j < N; ++j)
+        for (int64_t k = 0; k < K; ++k)
+            bt[(size_t)j * K + k] = oracle_bfloat16_bits_to_double(B[at(layoutB, ldb, k, j)]);
+    matmul_f64(M, N, K, a, bt, C, layoutC, ldc);
+    free(a);
+    free(bt);
+    return 0;
+}
+
 /*
  * Sampled form for sizes where the full product is too slow on a CPU: the same
  * definition evaluated only at the n listed positions (rows[t], cols[t]);
@@ -193,6 +252,26 @@ int oracle_gemm_f16_at(int64_t M, int64_t N, int64_t K,
         for (int64_t k = 0; k < K; ++k)
             acc += oracle_half_bits_to_double(A[at(layoutA, lda, rows[t], k)]) *
                    oracle_half_bits_to_double(B[at(layoutB, ldb, k, cols[t])]);
+        out[t] = acc;
+    }
+    return 0;
+}
+
+int oracle_gemm_bf16_at(int64_t M, int64_t N, int64_t K,
+                        const uint16_t *A, int layoutA, int64_t lda,
+                        const uint16_t *B, int layoutB, int64_t ldb,
+                        int64_t n, const int64_t *rows, const int64_t *cols, double *out)
+{
+    if (M < 0 || N < 0 || K < 0 || n < 0) return -1;
+    if (bad_matrix(A, layoutA, lda, M, K) || bad_matrix(B, layoutB, ldb, K, N)) return -1;
+    for (int64_t t = 0; t < n; ++t)
+        if (rows[t] < 0 || rows[t] >= M || cols[t] < 0 || cols[t] >= N) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        double acc = 0.0;
+        for (int64_t k = 0; k < K; ++k)
+            acc += oracle_bfloat16_bits_to_double(A[at(layoutA, lda, rows[t], k)]) *
+                   oracle_bfloat16_bits_to_double(B[at(layoutB, ldb, k, cols[t])]);
         out[t] = acc;
     }
     return 0;

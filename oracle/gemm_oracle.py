@@ -49,13 +49,16 @@ def _load():
         i64, p, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         full = [i64, i64, i64, p, i32, i64, p, i32, i64, p, i32, i64]
         samp = [i64, i64, i64, p, i32, i64, p, i32, i64, i64, p, p, p]
-        for name, sig in (("oracle_gemm_f32", full), ("oracle_gemm_f16", full),
-                          ("oracle_gemm_f32_at", samp), ("oracle_gemm_f16_at", samp)):
+        for name, sig in (("oracle_gemm_f32", full), ("oracle_gemm_f16", full), ("oracle_gemm_bf16", full),
+                          ("oracle_gemm_f32_at", samp), ("oracle_gemm_f16_at", samp),
+                          ("oracle_gemm_bf16_at", samp)):
             fn = getattr(lib, name)
             fn.argtypes = sig
             fn.restype = i32
         lib.oracle_half_bits_to_double.argtypes = [ctypes.c_uint16]
         lib.oracle_half_bits_to_double.restype = ctypes.c_double
+        lib.oracle_bfloat16_bits_to_double.argtypes = [ctypes.c_uint16]
+        lib.oracle_bfloat16_bits_to_double.restype = ctypes.c_double
         lib.oracle_num_threads.restype = i32
         lib.oracle_double_to_half_bits.argtypes = [ctypes.c_double]
         lib.oracle_double_to_half_bits.restype = ctypes.c_uint16
@@ -71,6 +74,10 @@ def num_threads():
 
 def half_bits_to_double(bits):
     return float(_load().oracle_half_bits_to_double(int(bits) & 0xFFFF))
+
+
+def bfloat16_bits_to_double(bits):
+    return float(_load().oracle_bfloat16_bits_to_double(int(bits) & 0xFFFF))
 
 
 def double_to_half_bits(value):
@@ -136,9 +143,15 @@ def gemm_f16_raw(M, N, K, A, layoutA, lda, B, layoutB, ldb, layoutC=ROW_MAJOR, l
     return _gemm("oracle_gemm_f16", np.uint16, M, N, K, A, layoutA, lda, B, layoutB, ldb, layoutC, ldc)
 
 
+def gemm_bf16_raw(M, N, K, A, layoutA, lda, B, layoutB, ldb, layoutC=ROW_MAJOR, ldc=0):
+    """bfloat16 operands (uint16 bit patterns); float64 result."""
+    return _gemm("oracle_gemm_bf16", np.uint16, M, N, K, A, layoutA, lda, B, layoutB, ldb, layoutC, ldc)
+
+
 def gemm(M, N, K, A, layoutA, B, layoutB, dtype):
-    """Packed operands -> logical M x N float64 array. dtype is 'f32' or 'f16'."""
-    fn = gemm_f32_raw if dtype == "f32" else gemm_f16_raw
+    """Packed operands -> logical M x N float64 array. dtype is 'f32', 'f16' or 'bf16'
+    (bf16: uint16 bit patterns)."""
+    fn = {"f32": gemm_f32_raw, "f16": gemm_f16_raw, "bf16": gemm_bf16_raw}[dtype]
     C, _ = fn(M, N, K, A, layoutA, 0, B, layoutB, 0, ROW_MAJOR, 0)
     return C.reshape(M, N)
 
@@ -152,7 +165,7 @@ def gemm_at(M, N, K, A, layoutA, lda, B, layoutB, ldb, rows, cols, dtype):
     rows = np.ascontiguousarray(rows, dtype=np.int64)
     cols = np.ascontiguousarray(cols, dtype=np.int64)
     out = np.full(max(rows.size, 1), np.nan, dtype=np.float64)
-    fn = lib.oracle_gemm_f32_at if dtype == "f32" else lib.oracle_gemm_f16_at
+    fn = {"f32": lib.oracle_gemm_f32_at, "f16": lib.oracle_gemm_f16_at, "bf16": lib.oracle_gemm_bf16_at}[dtype]
     rc = fn(M, N, K, A.ctypes.data, layoutA, lda, B.ctypes.data, layoutB, ldb,
             rows.size, rows.ctypes.data, cols.ctypes.data, out.ctypes.data)
     if rc != 0:
