@@ -147,7 +147,7 @@ def main():
                 "kernel": per_layout[dom]["kernel"], "flop_per_launch": flop,
                 "avg_launch_ms": per_layout[dom]["ms"]}
 
-    zero_data = fp16_out = None
+    zero_data = fp16_out = bf16 = None
     if not args.no_context:
         # --- context, not part of the timed step: the same four launches on all-zero operands.  With
         # N(0,1) data the part lowers its clock to stay inside its power limit; zeros do not toggle the
@@ -169,6 +169,18 @@ def main():
         fp16_out = {"workload": "f16f16_%dx%dx%d_NT (binary16 C)" % (S, S, S), "ms": round(pc16[0], 4),
                     "tflops": round(flop / pc16[0] / 1e9, 1), "kernel": g.last_config()}
         del C16
+
+        # --- context: the bfloat16 sibling on the same NT launch (same kernels, other MFMA instruction);
+        # N(0,1) entries rounded to bfloat16
+        Ab = torch.from_numpy(gi.bfloat16_bits(gi.round_to_bfloat16(A_np.astype(np.float32))).view(np.int16)).cuda()
+        Bb = torch.from_numpy(gi.bfloat16_bits(gi.round_to_bfloat16(B_np.astype(np.float32))).view(np.int16)).cuda()
+        dAb, _, dBb, _ = device_operands(Ab, Bb, "NT")
+        Cb = torch.empty(S * S, dtype=torch.float32, device="cuda")  # the headline results stay untouched
+        _, pcb = time_calls(g.gemm_bf16f32, [nt[:3] + (dAb, nt[4], 0, dBb, nt[7], 0, Cb) + nt[10:]],
+                            max(5, args.steps // 2), max(2, args.warmup // 2))
+        bf16 = {"workload": "bf16f32_%dx%dx%d_NT" % (S, S, S), "ms": round(pcb[0], 4),
+                "tflops": round(flop / pcb[0] / 1e9, 1), "kernel": g.last_config()}
+        del Ab, Bb, dAb, dBb, Cb
 
     # --- secondary workload (not part of the timed step): FP32 4096^3, A row-major, B column-major
     A32_np, B32_np = gi.make_problem(2000, 4096, 4096, 4096, "uniform", "f32")
@@ -194,7 +206,7 @@ def main():
         "per_layout": per_layout, "roofline": roofline, "fp32": fp32,
     }
     if zero_data is not None:
-        out["zero_data"], out["fp16_out"] = zero_data, fp16_out
+        out["zero_data"], out["fp16_out"], out["bf16"] = zero_data, fp16_out, bf16
     if not args.no_cpu_baseline:
         def gpu_rows(rows):
             return outs["NT"][: rows * S].cpu().numpy().reshape(rows, S)

@@ -30,6 +30,8 @@
  *   gemm_f16f32 : binary16 operands (passed as their 16-bit patterns), products
  *                 accumulated in binary32, binary32 C.
  *   gemm_f16f16 : the same, with C rounded to binary16 at the store.
+ *   gemm_bf16f32: bfloat16 operands (16-bit patterns: the upper half of the
+ *                 binary32 number of the same value), binary32 accumulation and C.
  *   The order in which the K products are added is unspecified.
  *
  * Execution
@@ -100,6 +102,19 @@ int gemm_f16f16(int64_t M, int64_t N, int64_t K,
                 const uint16_t *B, int layoutB, int64_t ldb,
                 uint16_t *C, int layoutC, int64_t ldc,
                 void *hip_stream);
+
+/*
+ * C = A*B, bfloat16 operands, binary32 accumulation and result: the same MatMul
+ * specification (Section 3.1) on the matrix instruction of Section 4.2 with the
+ * target's other 16-bit operand format (1 sign, 8 exponent, 7 fraction bits).
+ * Products of two bfloat16 numbers are exact in binary32; the sum is rounded as
+ * in gemm_f16f32.  Arguments, layouts and errors as for gemm_f16f32.
+ */
+int gemm_bf16f32(int64_t M, int64_t N, int64_t K,
+                 const uint16_t *A, int layoutA, int64_t lda,
+                 const uint16_t *B, int layoutB, int64_t ldb,
+                 float *C, int layoutC, int64_t ldc,
+                 void *hip_stream);
 
 /*
  * Kernel-configuration control (the paper tunes the block tile per input size,

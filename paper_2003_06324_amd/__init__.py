@@ -4,9 +4,9 @@ Everything is computed by the HIP kernels in csrc/; this package only loads
 libgemm_mi355x.so and marshals arguments.  There is no CPU fallback: if the
 library cannot be loaded, calls raise.
 """
-from .gemm import (COL_MAJOR, ROW_MAJOR, GemmError, config_names, force_config, gemm_f16f16,
-                   gemm_f16f32, gemm_f32, last_config, library_path, query_config, load_library, shutdown, status_string)
+from .gemm import (COL_MAJOR, ROW_MAJOR, GemmError, config_names, force_config, gemm_bf16f32,
+                   gemm_f16f16, gemm_f16f32, gemm_f32, last_config, library_path, query_config, load_library, shutdown, status_string)
 
-__all__ = ["ROW_MAJOR", "COL_MAJOR", "GemmError", "gemm_f32", "gemm_f16f32", "gemm_f16f16", "force_config",
+__all__ = ["ROW_MAJOR", "COL_MAJOR", "GemmError", "gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "force_config",
            "config_names", "query_config", "last_config", "status_string", "shutdown", "load_library",
            "library_path"]

@@ -10,6 +10,7 @@
 #include <map>
 #include <mutex>
 #include <string>
+#include <type_traits>
 
 using namespace gemm_gfx950;
 
@@ -18,6 +19,10 @@ GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 2)
 GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(_Float16, 128, 128, 2, 2)
 GEMM_DECLARE_TILE(_Float16, 64, 64, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 256, 256, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 256, 256, 2, 4)
+GEMM_DECLARE_TILE(__bf16, 128, 128, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 64, 64, 2, 2)
 GEMM_DECLARE_TILE(float, 256, 256, 2, 2)
 GEMM_DECLARE_TILE(float, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(float, 128, 128, 2, 2)
@@ -63,16 +68,20 @@ struct TileConfig {
     double f16_alone, f16_full; // microseconds per 64-k slab: one workgroup on a CU / CU fully occupied
     double f32_alone, f32_full; // same per 32-k f32 slab
     double general;             // slowdown of the register-staged (unaligned) path
-    launch_fn f16, f32;
+    launch_fn f16, f32, bf16;
 };
 
 // Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
 // under sustained MFMA load; these are not clock-peak figures).
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>},
-    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>},
-    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>},
-    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>},
+    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>,
+     launch_tile<__bf16, 256, 256, 2, 2>},
+    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>,
+     launch_tile<__bf16, 128, 128, 2, 2>},
+    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>,
+     launch_tile<__bf16, 64, 64, 2, 2>},
+    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>,
+     launch_tile<__bf16, 256, 256, 2, 4>},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -176,13 +185,16 @@ int get_workspace(size_t bytes, void **out)
     return GEMM_OK;
 }
 
-// T: operand type; TC: element type of C (float, or _Float16 for gemm_f16f16)
+// T: operand type (bfloat16 runs the binary16 path with the other MFMA instruction, so it shares
+// the binary16 slab times of the selection); TC: element type of C (float, or _Float16 for gemm_f16f16)
 template <typename T, typename TC>
 int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t lda,
               const void *B, int layB, int64_t ldb, TC *C, int layC, int64_t ldc, void *stream_)
 {
     constexpr bool f32 = sizeof(T) == 4;
     constexpr bool out16 = sizeof(TC) == 2;
+    constexpr bool bf16 = std::is_same<T, __bf16>::value;
+    const char *const type_name = f32 ? "f32" : (bf16 ? "bf16" : (out16 ? "f16f16" : "f16"));
     constexpr int64_t kMax = 2147483647LL - 256;
     if (M < 0 || N < 0 || K < 0) return GEMM_ERR_INVALID_ARG;
     if (lda < 0 || ldb < 0 || ldc < 0) return GEMM_ERR_INVALID_ARG;
@@ -191,7 +203,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     if (M > kMax || N > kMax || K > kMax) return GEMM_ERR_UNSUPPORTED;
     hipStream_t stream = (hipStream_t)stream_;
     if (M == 0 || N == 0) {
-        snprintf(t_last_config, sizeof t_last_config, "%s empty", f32 ? "f32" : "f16");
+        snprintf(t_last_config, sizeof t_last_config, "%s empty", type_name);
         return GEMM_OK;
     }
 
@@ -212,7 +224,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         const int blocks = (int)(cdiv(total, 256) < 65536 ? cdiv(total, 256) : 65536);
         hipLaunchKernelGGL(fill_zero_kernel<TC>, dim3(blocks), dim3(256), 0, stream, C, ldc, (int)M, (int)N);
         if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
-        snprintf(t_last_config, sizeof t_last_config, "%s zero-fill", f32 ? "f32" : "f16");
+        snprintf(t_last_config, sizeof t_last_config, "%s zero-fill", type_name);
         return GEMM_OK;
     }
 
@@ -274,7 +286,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         a.stream_c = (lines && (rounds || M * N * 4 <= (32LL << 20))) ? 1 : 0;
     }
     const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n * splits, 8)));
-    const launch_fn fn = f32 ? t.f32 : t.f16;
+    const launch_fn fn = f32 ? t.f32 : (bf16 ? t.bf16 : t.f16);
     const hipError_t launch_rc = fn(akc, bkc, aligned, grid, stream, a);
     if (launch_rc != hipSuccess) {
         if (getenv("GEMM_VERBOSE"))
@@ -288,7 +300,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
                            (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
         if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
     }
-    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d", f32 ? "f32" : (out16 ? "f16f16" : "f16"), t.name,
+    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d", type_name, t.name,
              akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits);
     return GEMM_OK;
 }
@@ -316,6 +328,13 @@ int gemm_f16f16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA,
 {
     return gemm_impl<_Float16, _Float16>(M, N, K, A, layoutA, lda, B, layoutB, ldb, (_Float16 *)C, layoutC, ldc,
                                          hip_stream);
+}
+
+int gemm_bf16f32(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA, int64_t lda,
+                 const uint16_t *B, int layoutB, int64_t ldb, float *C, int layoutC, int64_t ldc,
+                 void *hip_stream)
+{
+    return gemm_impl<__bf16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
 }
 
 int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen)

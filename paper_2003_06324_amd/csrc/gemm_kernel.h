@@ -38,6 +38,7 @@ namespace gemm_gfx950 {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef __fp16 fp16x4_t __attribute__((__vector_size__(4 * sizeof(__fp16))));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
@@ -71,6 +72,9 @@ struct KernelArgs {
 template <typename T> struct Elem;
 template <> struct Elem<_Float16> { static constexpr int EPC = 8, KG = 16, BK = KG * KGS; };
 template <> struct Elem<float>    { static constexpr int EPC = 4, KG = 8, BK = KG * KGS; };
+// bfloat16 shares every byte of the binary16 path (loads, LDS images, fragment reads move bit
+// patterns); only the MFMA instruction differs
+template <> struct Elem<__bf16>   { static constexpr int EPC = 8, KG = 16, BK = KG * KGS; };
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }        // vmcnt(n)
@@ -311,6 +315,7 @@ __device__ __forceinline__ void staged_store(GEMM_LDS(char) *dst, const Staged<T
 template <typename T> struct Frag;
 template <> struct Frag<_Float16> { typedef half8_t type; };
 template <> struct Frag<float> { typedef float4_t type; };
+template <> struct Frag<__bf16> { typedef bf16x8_t type; };
 
 // r0: first tile row of the 32-row block inside the slab image
 template <int R>
@@ -390,6 +395,17 @@ template <int R> struct Fetch<float, R, false> {
     static __device__ __forceinline__ float4_t get(const GEMM_LDS(char) *i, int r0, int kg, int l) { return fetch_f32_mc<R>(i, r0, kg, l); }
 };
 
+template <int R, bool KC> struct Fetch<__bf16, R, KC> {
+    static __device__ __forceinline__ bf16x8_t get(const GEMM_LDS(char) *i, int r0, int kg, int l)
+    {
+        return __builtin_bit_cast(bf16x8_t, Fetch<_Float16, R, KC>::get(i, r0, kg, l));
+    }
+};
+
+__device__ __forceinline__ void mma(float16_t &acc, const bf16x8_t &a, const bf16x8_t &b)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+}
 __device__ __forceinline__ void mma(float16_t &acc, const half8_t &a, const half8_t &b)
 {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);

@@ -1,0 +1,5 @@
+// Kernel instantiations: bfloat16 operands, 64x64 workgroup tile, 2x2 waves.
+#include "gemm_launch.h"
+namespace gemm_gfx950 {
+GEMM_INSTANTIATE_TILE(__bf16, 64, 64, 2, 2)
+}

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -46,7 +46,7 @@ def load_library():
     lib = ctypes.CDLL(_LIB_PATH)
     i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
     sig = [i64, i64, i64, p, i32, i64, p, i32, i64, p, i32, i64, p]
-    for name in ("gemm_f32", "gemm_f16f32", "gemm_f16f16"):
+    for name in ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32"):
         fn = getattr(lib, name)
         fn.argtypes = sig
         fn.restype = i32
@@ -104,6 +104,13 @@ def gemm_f16f16(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stre
     """C = A*B, binary16 operands, binary32 accumulation, C rounded to binary16 (16-bit patterns)."""
     rc = load_library().gemm_f16f16(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
                                     _ptr(C), layoutC, ldc, stream or None)
+    return _check(rc) if check else rc
+
+
+def gemm_bf16f32(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stream=None, check=True):
+    """C = A*B, bfloat16 operands (16-bit patterns), binary32 accumulation and result."""
+    rc = load_library().gemm_bf16f32(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
+                                     _ptr(C), layoutC, ldc, stream or None)
     return _check(rc) if check else rc
 
 

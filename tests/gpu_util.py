@@ -4,12 +4,14 @@ import numpy as np
 
 import gemm_inputs as gi
 
-TOL = {"f32": 1e-6, "f16": 2e-4}          # max|C-Cref| / (K max|A| max|B|), the stated bar
+# max|C-Cref| / (K max|A| max|B|), the stated bar; bfloat16 operands take the binary16 one: the
+# products are exact in binary32 in both cases and the accumulation is the same
+TOL = {"f32": 1e-6, "f16": 2e-4, "bf16": 2e-4}
 # Stricter internal bar, max|C-Cref| / (K rms|A| rms|B|) <= 8 * 2^-24: binary32 accumulation
 # of K terms of size ~rms^2 drifts by about 2^-24 * K * rms^2 / sqrt(2) (random walk of the
 # per-add roundings, each ~2^-24 of a partial sum ~sqrt(k) rms^2); 8 leaves room for the
 # maximum over all entries.  One dropped or doubled term costs ~rms^2, i.e. 1/K >> the bar.
-TIGHT = {"f32": 8 * 2.0 ** -24, "f16": 8 * 2.0 ** -24}
+TIGHT = {"f32": 8 * 2.0 ** -24, "f16": 8 * 2.0 ** -24, "bf16": 8 * 2.0 ** -24}
 
 
 def to_device(buf):
@@ -24,7 +26,8 @@ def to_device(buf):
 def run_gpu(dtype, A, B, la, lb, lc=gi.ROW_MAJOR, pads=(0, 0, 0), offsets=(0, 0, 0), force=None,
             return_config=False, out="f32"):
     """HIP path on logical matrices A (M x K), B (K x N); returns logical float32 C
-    (out="f16": the binary16-output entry point, returns a float16 array).
+    (out="f16": the binary16-output entry point, returns a float16 array).  dtype "bf16": A and
+    B are float32 arrays holding bfloat16 values, handed over as their 16-bit patterns.
 
     pads: extra leading-dimension elements per operand (padding is NaN-filled and, for C,
     checked to be untouched).  offsets: element offsets of each base pointer inside its
@@ -36,16 +39,18 @@ def run_gpu(dtype, A, B, la, lb, lc=gi.ROW_MAJOR, pads=(0, 0, 0), offsets=(0, 0,
     lda = (K if la == gi.ROW_MAJOR else M) + pads[0]
     ldb = (N if lb == gi.ROW_MAJOR else K) + pads[1]
     ldc = (N if lc == gi.ROW_MAJOR else M) + pads[2]
-    esz = 2 if dtype == "f16" else 4
+    esz = 4 if dtype == "f32" else 2
     bufA = np.concatenate([np.full(offsets[0], np.nan, A.dtype), gi.store(A, la, lda)])
     bufB = np.concatenate([np.full(offsets[1], np.nan, B.dtype), gi.store(B, lb, ldb)])
+    if dtype == "bf16":
+        bufA, bufB = gi.bfloat16_bits(bufA).view(np.int16), gi.bfloat16_bits(bufB).view(np.int16)
     dA, dB = to_device(bufA), to_device(bufB)
     c_major = M if lc == gi.ROW_MAJOR else N
     c_minor = N if lc == gi.ROW_MAJOR else M
     c_len = ((c_major - 1) * ldc + c_minor) if (M > 0 and N > 0) else 0
     c_np, c_torch, c_esz = (np.float32, torch.float32, 4) if out == "f32" else (np.float16, torch.float16, 2)
     dC = torch.full((offsets[2] + c_len + 8,), float("nan"), dtype=c_torch, device="cuda")
-    fn = g.gemm_f32 if dtype == "f32" else (g.gemm_f16f32 if out == "f32" else g.gemm_f16f16)
+    fn = {"f32": g.gemm_f32, "bf16": g.gemm_bf16f32, "f16": g.gemm_f16f32 if out == "f32" else g.gemm_f16f16}[dtype]
     stream = torch.cuda.current_stream().cuda_stream
     g.force_config(force)
     try:
