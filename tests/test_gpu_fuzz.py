@@ -54,3 +54,22 @@ def test_random_cases_bit_exact(oracle, chunk):
             assert np.array_equal(C.view(np.uint16), want.view(np.uint16)), (what, cfg)
         else:
             assert np.array_equal(C, exact.astype(np.float32)), (what, cfg)
+
+
+@pytest.mark.parametrize("chunk", range(3))
+def test_random_cases_bit_exact_bfloat16(oracle, chunk):
+    # the 16-bit draws of the same generator, as bfloat16 patterns through gemm_bf16f32
+    rng = np.random.default_rng(30240 + chunk)
+    done = 0
+    while done < 25:
+        dtype, M, N, K, la, lb, lc, pads, offs, force, _ = draw_case(rng)
+        seed = int(rng.integers(1, 1 << 30))
+        if dtype != "f16":
+            continue
+        done += 1
+        A, B = gi.make_problem(seed, M, N, K, "int", "bf16")
+        exact = oracle.gemm(M, N, K, gi.bfloat16_bits(A), gi.ROW_MAJOR, gi.bfloat16_bits(B), gi.ROW_MAJOR, "bf16")
+        what = (chunk, done, M, N, K, la, lb, lc, pads, offs, force)
+        C, cfg = run_gpu("bf16", A, B, la, lb, lc, pads=pads, offsets=offs, force=force, return_config=True)
+        assert cfg.startswith("bf16 ")
+        assert np.array_equal(C, exact.astype(np.float32)), (what, cfg)
