@@ -127,9 +127,11 @@ int gemm_force_config(const char *name);
 
 /*
  * The configuration the selection would pick (or the forced one), without touching the
- * device: elem_bytes is 2 (binary16 operands) or 4 (binary32); aligned != 0 means both
- * operands qualify for the direct-load kernels (16-byte aligned bases and leading
- * dimensions).  Writes "<tile>:s<splits>" into buf (NUL-terminated, truncated to buflen).
+ * device: elem_bytes is 2 (16-bit operands) or 4 (binary32); aligned is the alignment in
+ * bytes that the bases and leading dimensions of A and B share: 16 or more (or 1, "yes")
+ * means they qualify for the direct-load kernels, 8, 4 (or 0, "no") the register-staged
+ * kernels, 2 the register-staged kernels on operands whose 16-byte loads the memory
+ * pipeline has to split.  Writes "<tile>:s<splits>" into buf (NUL-terminated, truncated to buflen).
  * This is the host side of the per-size tuning of Section 5.3, exposed so that it can be
  * tested without a GPU.
  */

@@ -86,20 +86,21 @@ struct TileConfig {
     int wg_per_cu;              // resident workgroups per CU (LDS-limited)
     double f16_alone, f16_full; // microseconds per 64-k slab: one workgroup on a CU / CU fully occupied
     double f32_alone, f32_full; // same per 32-k f32 slab
-    double general;             // slowdown of the register-staged (unaligned) path
+    double general;             // slowdown of the register-staged (unaligned) path, 16-bit operands
+    int depth;                  // slabs that path keeps in flight in registers
     launch_fn f16, f32, bf16;
 };
 
 // Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
 // under sustained MFMA load; these are not clock-peak figures).
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>,
+    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, 1, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>,
      launch_tile<__bf16, 256, 256, 2, 2>},
-    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>,
+    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, 3, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>,
      launch_tile<__bf16, 128, 128, 2, 2>},
-    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>,
+    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, 4, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>,
      launch_tile<__bf16, 64, 64, 2, 2>},
-    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>,
+    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, 1, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>,
      launch_tile<__bf16, 256, 256, 2, 4>},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
@@ -119,8 +120,10 @@ int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // how many workgroups share a CU), HBM traffic for the unique bytes (limited by how many
 // bytes the resident workgroups keep in flight), and L2->CU traffic for all the bytes the
 // workgroups pull; plus launch/fill/drain and, with K slices, the reduce pass.
+// path: 0 = direct-load kernels, 1 = register-staged loads, 2 = register-staged loads of operands
+// that are only 2-byte aligned (each 16-byte load is then split up by the memory pipeline)
 double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64_t KT, int splits, bool f32,
-                     bool aligned)
+                     int path)
 {
     const int64_t tiles = cdiv(M, t.BM) * cdiv(N, t.BN);
     const int64_t per = cdiv(KT, splits);
@@ -131,11 +134,13 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
     const int64_t share = cdiv(W, NUM_CU) < t.wg_per_cu ? cdiv(W, NUM_CU) : t.wg_per_cu;
     const double alone = f32 ? t.f32_alone : t.f16_alone, full = f32 ? t.f32_full : t.f16_full;
     double slab = alone + (t.wg_per_cu > 1 ? (full - alone) * (double)(share - 1) / (t.wg_per_cu - 1) : 0.0);
-    if (!aligned) {
-        // the register-staged path prefetches one slab ahead only: a slab cannot take less than
-        // about one global-load round trip, shared among the workgroups on the CU
-        slab *= t.general;
-        if (slab < 1.2 / (double)share) slab = 1.2 / (double)share;
+    if (path != 0) {
+        // the register-staged path keeps `depth` slabs in flight per workgroup: a slab cannot take
+        // less than that share of a global-load round trip
+        // (binary32 slabs are bound by their MFMA time: measured within 5 % of the direct path)
+        slab *= f32 ? 1.05 : t.general * (path == 2 ? 1.5 : 1.0);
+        const double floor = 1.2 / ((double)share * t.depth);
+        if (slab < floor) slab = floor;
     }
     const double t_mfma = rounds * ((double)per * slab + 1.0);
     const double esz = f32 ? 4.0 : 2.0;
@@ -150,7 +155,7 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
     return cost;
 }
 
-void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, bool aligned, int &tile, int &splits)
+void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int &tile, int &splits)
 {
     double best = 1e300;
     tile = g_forced_tile >= 0 ? g_forced_tile : 0;
@@ -160,7 +165,7 @@ void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, bool aligned,
         for (int s = 1; s <= 32; s *= 2) {
             const int cand = g_forced_splits > 0 ? g_forced_splits : s;
             if (cand > 1 && cand > KT) break;
-            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, aligned);
+            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, path);
             if (c < best) { best = c; tile = t; splits = cand; }
             if (g_forced_splits > 0) break;
         }
@@ -257,12 +262,15 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     // the direct loaders address a tile with 32-bit byte offsets from its origin
     const bool ld32 = 256 * lda * (int64_t)sizeof(T) < (1LL << 31) && 256 * ldb * (int64_t)sizeof(T) < (1LL << 31);
     if (!ld32) aligned = false;
+    const uintptr_t low_bits = (uintptr_t)A | (uintptr_t)B | (uintptr_t)(lda * (int64_t)sizeof(T)) |
+                               (uintptr_t)(ldb * (int64_t)sizeof(T));
+    const int path = aligned ? 0 : ((low_bits & 3) != 0 ? 2 : 1);
 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, K, KT, f32, aligned, tile, splits);
+        choose(M, N, K, KT, f32, path, tile, splits);
     }
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
@@ -373,7 +381,7 @@ int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int align
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, K, KT, f32, aligned != 0, tile, splits);
+        choose(M, N, K, KT, f32, aligned == 1 || aligned >= 16 ? 0 : (aligned == 2 ? 2 : 1), tile, splits);
     }
     const int64_t per = cdiv(KT, splits);
     splits = (int)cdiv(KT, per);  // no empty slices, as in the launch path

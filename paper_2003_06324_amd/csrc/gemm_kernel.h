@@ -685,9 +685,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     if (!ALIGNED) {
         // Operands that are not 16-byte aligned: full slabs go through registers into two LDS
         // buffers (the same image as the direct loads make).  Per slab s: k-groups 0,1 multiply;
-        // k-group 2 also writes slab s+1 (in registers since the previous slab) to the other
+        // k-group 2 also writes slab s+1 (in registers since an earlier slab) to the other
         // buffer; wait for the own LDS traffic, one barrier; k-group 3 also issues the global
-        // loads of slab s+2 into the freed registers and fetches slab s+1's first operands.
+        // loads of a later slab into the freed registers and fetches slab s+1's first operands.
         // Rows (or whole granules) past the M/N edge re-read a valid one as in the direct
         // path.  A granule of an M/N-contiguous operand that straddles the edge is read whole:
         // its tail is the padding or the start of the next k-row, lands in tile rows past the
@@ -706,27 +706,49 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             DirectLoader<T, BN, NW, BKC> lb;
             la.init(A, p.lda, m0, p.M, k_done, wave, lane);
             lb.init(B, p.ldb, n0, p.N, k_done, wave, lane);
-            uint4_t ra[NVA], rb[NVB];
-            auto fetch_regs = [&](int q) {
-                if (q < NVA) ra[q] = la.fetch1(q);
-                else rb[q - NVA] = lb.fetch1(q - NVA);
+            // DEPTH register sets: slab s waits in set s % DEPTH from the k-group 3 that issued
+            // its loads (DEPTH slabs earlier) to the k-group 2 that writes it to LDS.  The small
+            // tiles multiply a slab in far less than a global-load round trip, so they keep
+            // several slabs in flight; the 256x256 tiles have no registers to spare and keep one.
+            constexpr int DEPTH = BM * BN <= 64 * 64 ? 4 : (BM * BN <= 128 * 128 ? 3 : 1);
+            uint4_t ra[DEPTH][NVA], rb[DEPTH][NVB];
+            auto fetch_set = [&](auto set_tag) {
+                constexpr int S = decltype(set_tag)::value;
+                return [&](int q) {
+                    if (q < NVA) ra[S][q] = la.fetch1(q);
+                    else rb[S][q - NVA] = lb.fetch1(q - NVA);
+                };
             };
             GEMM_LDS(char) *wA = lds, *wB = lds + SLOT;  // where the registers go next
-            auto store_regs = [&](int q) {
-                if (q < NVA) la.store1(wA, wave, lane, q, ra[q]);
-                else lb.store1(wB, wave, lane, q - NVA, rb[q - NVA]);
+            auto store_set = [&](auto set_tag) {
+                constexpr int S = decltype(set_tag)::value;
+                return [&](int q) {
+                    if (q < NVA) la.store1(wA, wave, lane, q, ra[S][q]);
+                    else lb.store1(wB, wave, lane, q - NVA, rb[S][q - NVA]);
+                };
             };
             typedef std::integral_constant<int, NVA + NVB> LAB;
+            typedef std::integral_constant<int, 0> SET0;
+            // slab 0 -> set 0 -> first LDS buffer; then slabs 1 .. DEPTH into sets 1 .. DEPTH-1, 0
+            // (past the end of K the loaders stay on the last slab, re-fetched and never used)
 #pragma unroll
-            for (int q = 0; q < NVA + NVB; ++q) fetch_regs(q);
+            for (int q = 0; q < NVA + NVB; ++q) fetch_set(SET0())(q);
             la.advance(1 < n);
             lb.advance(1 < n);
 #pragma unroll
-            for (int q = 0; q < NVA + NVB; ++q) store_regs(q);
+            for (int q = 0; q < NVA + NVB; ++q) store_set(SET0())(q);
+            auto prologue_fetch = [&](auto d_tag) {
+                constexpr int D = decltype(d_tag)::value;
 #pragma unroll
-            for (int q = 0; q < NVA + NVB; ++q) fetch_regs(q);
-            la.advance(2 < n);
-            lb.advance(2 < n);
+                for (int q = 0; q < NVA + NVB; ++q) fetch_set(std::integral_constant<int, D % DEPTH>())(q);
+                la.advance(D + 1 < n);
+                lb.advance(D + 1 < n);
+            };
+            prologue_fetch(std::integral_constant<int, 1>());
+            if constexpr (DEPTH >= 2) prologue_fetch(std::integral_constant<int, 2>());
+            if constexpr (DEPTH >= 3) prologue_fetch(std::integral_constant<int, 3>());
+            if constexpr (DEPTH >= 4) prologue_fetch(std::integral_constant<int, 4>());
+            static_assert(DEPTH <= 4, "prologue written for up to four register sets");
             __syncthreads();
 
             frag_t fa[2][FM], fb[2][FN];
@@ -736,20 +758,39 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 #pragma unroll
             for (int i = 1; i < FM; ++i) fa[0][i] = Fetch<T, BM, AKC>::get(lds, wm * TM + i * 32, 0, lane);
             int cur = 0;
-            for (int sl = 0; sl < n - 1; ++sl) {
+            int sl = 0;
+            // multiplies slab sl, moves slab sl+1 (register set SET) to LDS, refills the set with
+            // slab sl+1+DEPTH
+            auto slab_body = [&](auto set_tag) {
                 const GEMM_LDS(char) *cA = lds + (2 * cur) * SLOT, *cB = cA + SLOT;
                 wA = lds + (2 * (cur ^ 1)) * SLOT;
                 wB = wA + SLOT;
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 1, true, no_load, L0());
                 kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
-                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, store_regs, LAB());
+                kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, store_set(set_tag), LAB());
                 // own LDS writes and reads done; the loads issued below stay in flight
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
                 barrier_keep_loads();
-                kgroup(fa[1], fb[1], fa[0], fb[0], wA, wB, 0, true, fetch_regs, LAB());
-                la.advance(sl + 3 < n);
-                lb.advance(sl + 3 < n);
+                kgroup(fa[1], fb[1], fa[0], fb[0], wA, wB, 0, true, fetch_set(set_tag), LAB());
+                la.advance(sl + 2 + DEPTH < n);
+                lb.advance(sl + 2 + DEPTH < n);
                 cur ^= 1;
+                ++sl;
+            };
+            // sl is a multiple of DEPTH at the top of the loop, so slab sl+1+d sits in set (1+d) % DEPTH
+            while (sl + DEPTH <= n - 1) {
+                slab_body(std::integral_constant<int, 1 % DEPTH>());
+                if constexpr (DEPTH >= 2) slab_body(std::integral_constant<int, 2 % DEPTH>());
+                if constexpr (DEPTH >= 3) slab_body(std::integral_constant<int, 3 % DEPTH>());
+                if constexpr (DEPTH >= 4) slab_body(std::integral_constant<int, 4 % DEPTH>());
+            }
+            if constexpr (DEPTH >= 2) {
+                const int rest = n - 1 - sl;  // 0 .. DEPTH-1 slabs still have a successor
+                if (rest > 0) slab_body(std::integral_constant<int, 1 % DEPTH>());
+                if (rest > 1) slab_body(std::integral_constant<int, 2 % DEPTH>());
+                if constexpr (DEPTH >= 4) {
+                    if (rest > 2) slab_body(std::integral_constant<int, 3 % DEPTH>());
+                }
             }
             prefetch_leftover(k_done + n * BK);
             {

@@ -115,9 +115,10 @@ def gemm_bf16f32(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, str
 
 
 def query_config(elem_bytes, M, N, K, aligned=True):
-    """The "<tile>:s<splits>" the selection picks for this shape (host only, nothing is launched)."""
+    """The "<tile>:s<splits>" the selection picks for this shape (host only, nothing is launched).
+    aligned: True / False, or the common alignment of bases and leading dimensions in bytes."""
     buf = ctypes.create_string_buffer(64)
-    _check(load_library().gemm_query_config(elem_bytes, M, N, K, 1 if aligned else 0, buf, 64))
+    _check(load_library().gemm_query_config(elem_bytes, M, N, K, int(aligned), buf, 64))
     return buf.value.decode()
 
 

@@ -6,6 +6,10 @@ calibrated on this output.
 
     python3 -m paper_2003_06324_amd.tune_sweep            # default shape list
     python3 -m paper_2003_06324_amd.tune_sweep f16 1536 1024 2048 NT
+    python3 -m paper_2003_06324_amd.tune_sweep unaligned  # only the shapes with offset bases
+
+A shape may carry a byte offset added to both operand bases: operands that are not 16-byte
+aligned run the register-staged kernels, and 2-byte aligned ones a slower class of those.
 """
 import os
 import sys
@@ -23,6 +27,12 @@ DEFAULT_SHAPES = [
     ("f16", 1024, 4096, 2048, "NN"), ("f16", 4096, 1024, 1024, "TT"),
     ("f32", 1024, 1024, 1024, "NT"), ("f32", 2048, 2048, 2048, "NT"),
 ]
+UNALIGNED_SHAPES = [
+    ("f16", 2048, 2048, 2048, "NT", 8), ("f16", 2048, 2048, 2048, "NT", 2), ("f16", 2048, 2048, 2048, "TN", 4),
+    ("f16", 1024, 1024, 1024, "NT", 2), ("f16", 512, 512, 512, "NT", 8), ("f16", 1536, 1024, 2048, "NT", 8),
+    ("f16", 4096, 4096, 1024, "NT", 2), ("f16", 4096, 4096, 4096, "NT", 8),
+    ("f32", 2048, 2048, 2048, "NT", 4), ("f32", 1024, 1024, 1024, "NN", 8),
+]
 
 
 def main():
@@ -30,9 +40,12 @@ def main():
     import gemm_inputs as gi
     import paper_2003_06324_amd as g
 
-    shapes = DEFAULT_SHAPES
-    if len(sys.argv) == 6:
-        shapes = [(sys.argv[1], int(sys.argv[2]), int(sys.argv[3]), int(sys.argv[4]), sys.argv[5])]
+    shapes = DEFAULT_SHAPES + UNALIGNED_SHAPES
+    if len(sys.argv) == 2 and sys.argv[1] == "unaligned":
+        shapes = UNALIGNED_SHAPES
+    if len(sys.argv) >= 6:
+        shapes = [(sys.argv[1], int(sys.argv[2]), int(sys.argv[3]), int(sys.argv[4]), sys.argv[5]) +
+                  ((int(sys.argv[6]),) if len(sys.argv) > 6 else ())]
     stream = torch.cuda.current_stream().cuda_stream
 
     def timed(fn, iters):
@@ -48,14 +61,17 @@ def main():
         return e0.elapsed_time(e1) / iters * 1e3  # microseconds
 
     worst = 1.0
-    for dt, M, N, K, lay in shapes:
+    for shape in shapes:
+        dt, M, N, K, lay = shape[:5]
+        off = shape[5] if len(shape) > 5 else 0
         tdt = torch.float16 if dt == "f16" else torch.float32
-        A = torch.randn(M * K, device="cuda", dtype=tdt)
-        B = torch.randn(K * N, device="cuda", dtype=tdt)
+        A = torch.randn(M * K + 8, device="cuda", dtype=tdt)
+        B = torch.randn(K * N + 8, device="cuda", dtype=tdt)
         C = torch.empty(M * N, device="cuda", dtype=torch.float32)
         la, lb = gi.LAYOUTS[lay]
         call = g.gemm_f16f32 if dt == "f16" else g.gemm_f32
-        fn = lambda: call(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
+        pA, pB = A.data_ptr() + off, B.data_ptr() + off
+        fn = lambda: call(M, N, K, pA, la, 0, pB, lb, 0, C, gi.ROW_MAJOR, 0, stream)
         results = []
         for tile in g.config_names():
             for s in (1, 2, 4, 8, 16, 32):
@@ -71,8 +87,8 @@ def main():
         best = (timed(fn, 20), results[0][1], results[0][2])
         g.force_config(None)
         worst = max(worst, t_auto / best[0])
-        print("%s %dx%dx%d %s: auto %.1f us [%s] | best %.1f us %s:s%d | auto/best %.2f | %.1f TFLOP/s" % (
-            dt, M, N, K, lay, t_auto, auto_cfg, best[0], best[1], best[2], t_auto / best[0],
+        print("%s %dx%dx%d %s%s: auto %.1f us [%s] | best %.1f us %s:s%d | auto/best %.2f | %.1f TFLOP/s" % (
+            dt, M, N, K, lay, " +%dB" % off if off else "", t_auto, auto_cfg, best[0], best[1], best[2], t_auto / best[0],
             2.0 * M * N * K / t_auto / 1e6), flush=True)
     print("worst auto/best ratio: %.2f" % worst)
 

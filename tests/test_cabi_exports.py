@@ -61,6 +61,17 @@ def test_selection_of_tile_and_k_slices():
     assert q(2, 4097, 3073, 1025, aligned=False) == "t256x256w8:s1"
     assert q(2, 1000, 1500, 2000, aligned=False) == "t64x64:s1"
     assert q(4, 4096, 4096, 4096) == "t256x256:s1"
+    # register-staged kernels (bases or leading dimensions not 16-byte aligned): the alignment
+    # class is passed in bytes; mid-size shapes take the 128x128 tile, which keeps three slabs in
+    # flight in registers, and small ones are not cut into K slices
+    for align in (8, 4, 2):
+        assert q(2, 2048, 2048, 2048, aligned=align) == "t128x128:s1"
+        assert q(2, 1024, 1024, 1024, aligned=align) == "t64x64:s1"
+        assert q(2, 512, 512, 512, aligned=align) == "t64x64:s1"
+        assert q(2, 4096, 4096, 1024, aligned=align) == "t256x256w8:s1"
+    assert q(2, 2048, 2048, 2048, aligned=16) == q(2, 2048, 2048, 2048, aligned=True)
+    assert q(2, 2048, 2048, 2048, aligned=8) == q(2, 2048, 2048, 2048, aligned=False)
+    assert q(4, 2048, 2048, 2048, aligned=4) == "t128x128:s1"
     assert q(4, 256, 256, 256) == "t64x64:s1"
     # never more slices than K slabs (64 k for binary16, 32 k for binary32), none without K to spare
     for K in (1, 63, 64, 65, 200, 1000):
