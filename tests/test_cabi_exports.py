@@ -91,3 +91,25 @@ def test_selection_of_tile_and_k_slices():
     assert q(2, 8192, 8192, 130) == "t128x128:s3"
     g.force_config(None)
     assert g.load_library().gemm_query_config(3, 1, 1, 1, 1, None, 0) == -1
+
+
+def test_header_is_plain_c():
+    """include/gemm.h must be usable from C: no C++ or HIP types in the boundary."""
+    import subprocess
+    import tempfile
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "use_gemm.c")
+        with open(src, "w") as f:
+            f.write('#include "gemm.h"\n'
+                    "int (*const p_f32)(int64_t, int64_t, int64_t, const float *, int, int64_t, const float *, int, int64_t,\n"
+                    "                   float *, int, int64_t, void *) = gemm_f32;\n"
+                    "int layouts(void) { return GEMM_ROW_MAJOR + GEMM_COL_MAJOR + GEMM_OK + GEMM_ERR_WORKSPACE; }\n")
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I" + os.path.join(ROOT, "include"), src], check=True)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "single-GPU" in (r.stderr + r.stdout)
