@@ -32,7 +32,9 @@
  *   gemm_f16f16 : the same, with C rounded to binary16 at the store.
  *   gemm_bf16f32: bfloat16 operands (16-bit patterns: the upper half of the
  *                 binary32 number of the same value), binary32 accumulation and C.
- *   The order in which the K products are added is unspecified.
+ *   The order in which the K products are added is unspecified.  Subnormal
+ *   operands and results are kept (nothing is flushed to zero); NaN and
+ *   infinity propagate through the elements of A and B only.
  *
  * Execution
  *   Work is enqueued on hip_stream (a hipStream_t cast to void*; NULL is the
