@@ -39,11 +39,17 @@
  * Execution
  *   Work is enqueued on hip_stream (a hipStream_t cast to void*; NULL is the
  *   default stream) of the current device.  The call does not synchronise with
- *   the host.  Calls that use no K-slices only launch kernels and can be
- *   recorded into a HIP graph; calls that do may grow the workspace first.  Shapes that are split along K use a per-device workspace that
- *   the library grows with hipMalloc on demand and frees in gemm_shutdown();
- *   calls issued concurrently on different streams of one device must not both
- *   need the workspace.
+ *   the host, on any path.  Shapes that are split along K keep their partial
+ *   sums in a workspace that belongs to the (device, stream) pair: calls on
+ *   different streams never share one, calls on one stream are ordered by the
+ *   stream, and host threads that share a stream are serialised by the library
+ *   for the duration of the launches.  A workspace that is too small is
+ *   replaced by a larger one with hipMalloc (the old one is kept until
+ *   gemm_shutdown(), since earlier work may still use it), so such a call can
+ *   be recorded into a HIP graph only once its stream's workspace has reached
+ *   the size it needs, e.g. after the same call was made once outside the
+ *   capture; calls that use no K-slices only launch kernels and can always be
+ *   captured.
  *
  * Sizes
  *   M, N, K >= 0 and each below 2^31 - 256.  M == 0 or N == 0: nothing is
@@ -121,11 +127,36 @@ int gemm_bf16f32(int64_t M, int64_t N, int64_t K,
 /*
  * Kernel-configuration control (the paper tunes the block tile per input size,
  * Section 5.3; here a heuristic picks it and this hook overrides it).
- * name is "auto" / NULL for the heuristic, or "<tile>" or "<tile>:s<splits>",
- * e.g. "t256x256", "t128x128:s4".  Returns GEMM_ERR_UNSUPPORTED for an unknown
- * name.  The setting is process-wide.
+ * name is "auto" / NULL for the heuristic, or "<tile>[:s<slices>][:safe][:direct|:staged]" with
+ * <tile> a configuration name or "auto", e.g. "t256x256", "t128x128:s4",
+ * "auto:s2:safe".  A slice count beyond the number of K slabs means one slab
+ * per slice.  ":safe" runs the same kernels with every hand-over of a
+ * shared-memory buffer preceded by a wait for all outstanding memory operations
+ * and a full barrier (the paper notes, Section 4.1, that removing
+ * synchronisation can introduce races: this is the variant to compare against
+ * when one is suspected).  ":direct" stores C straight from the accumulator
+ * registers (the path edge tiles always take), ":staged" stages whole rows of
+ * every interior tile through shared memory (Section 3.2, "Epilog") wherever
+ * the rows of C start on 16-byte boundaries; without either the library picks
+ * by shape.  Returns GEMM_ERR_UNSUPPORTED for an unknown name.
+ * The setting is process-wide.
  */
 int gemm_force_config(const char *name);
+
+/*
+ * Re-calibration of the selection's cost model (Section 5.3 tunes per input
+ * size by measurement; the model's constants were measured on one part):
+ * multiplies one term by factor (> 0; 1 = as measured).  term < 0 resets all.
+ * Process-wide; GEMM_ERR_INVALID_ARG for an unknown term or factor <= 0.
+ */
+enum {
+    GEMM_COST_SLAB = 0,  /* time a workgroup needs per K slab */
+    GEMM_COST_HBM = 1,   /* sustained HBM rate (larger = faster memory) */
+    GEMM_COST_L2 = 2,    /* sustained L2-to-CU rate */
+    GEMM_COST_FIXED = 3, /* launch, pipeline fill and reduce-pass latencies */
+    GEMM_COST_TERMS = 4
+};
+int gemm_cost_model_scale(int term, double factor);
 
 /*
  * The configuration the selection would pick (or the forced one), without touching the
@@ -153,7 +184,7 @@ const char *gemm_last_config(void);
 /* Text for a status code (static storage). */
 const char *gemm_status_string(int status);
 
-/* Frees the per-device workspaces.  Safe to call more than once. */
+/* Frees every K-slice workspace (waits for the work that still uses them).  Safe to call more than once. */
 int gemm_shutdown(void);
 
 #ifdef __cplusplus

@@ -4,9 +4,9 @@ Everything is computed by the HIP kernels in csrc/; this package only loads
 libgemm_mi355x.so and marshals arguments.  There is no CPU fallback: if the
 library cannot be loaded, calls raise.
 """
-from .gemm import (COL_MAJOR, ROW_MAJOR, GemmError, config_names, force_config, gemm_bf16f32,
+from .gemm import (COL_MAJOR, COST_FIXED, COST_HBM, COST_L2, COST_SLAB, ROW_MAJOR, GemmError, config_names, cost_model_scale, force_config, gemm_bf16f32,
                    gemm_f16f16, gemm_f16f32, gemm_f32, last_config, library_path, query_config, load_library, shutdown, status_string)
 
 __all__ = ["ROW_MAJOR", "COL_MAJOR", "GemmError", "gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "force_config",
-           "config_names", "query_config", "last_config", "status_string", "shutdown", "load_library",
+           "config_names", "query_config", "cost_model_scale", "COST_SLAB", "COST_HBM", "COST_L2", "COST_FIXED", "last_config", "status_string", "shutdown", "load_library",
            "library_path"]

@@ -11,6 +11,7 @@
 #include <mutex>
 #include <string>
 #include <type_traits>
+#include <vector>
 
 using namespace gemm_gfx950;
 
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(TC *C, int64_t ldc, int 
     }
 }
 
-constexpr int NUM_CU = 256;
+constexpr int kDefaultNumCU = 256;  // MI355X; the launch path asks the device (gemm_query_config uses this)
 
 struct TileConfig {
     const char *name;
@@ -108,8 +109,22 @@ constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 std::mutex g_mutex;
 int g_forced_tile = -1;    // -1: heuristic
 int g_forced_splits = 0;   // 0: heuristic
+bool g_forced_safe = false;
+int g_store_mode = 0;  // 0: by shape; 1: ":direct", C straight from registers; 2: ":staged", through LDS where possible
+double g_cost_scale[GEMM_COST_TERMS] = {1.0, 1.0, 1.0, 1.0};
+
+// K-slice workspaces: one per (device, stream).  Work on one stream is ordered, so a stream's
+// buffer is never used by two launches at once; different streams never share one.  A buffer
+// that has become too small is retired, not freed (earlier launches may still use it and
+// hipFree would wait for the whole device): gemm_shutdown() frees everything.  Sizes at least
+// double on growth, so the retired buffers of a stream add up to less than its live one.
 struct Workspace { void *ptr = nullptr; size_t bytes = 0; };
-std::map<int, Workspace> g_workspace;
+struct DeviceState {
+    int num_cu = 0;
+    std::map<hipStream_t, Workspace> ws;
+    std::vector<void *> retired;
+};
+std::map<int, DeviceState> g_dev;
 
 thread_local char t_last_config[128] = "none";
 
@@ -123,8 +138,9 @@ int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // path: 0 = direct-load kernels, 1 = register-staged loads, 2 = register-staged loads of operands
 // that are only 2-byte aligned (each 16-byte load is then split up by the memory pipeline)
 double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64_t KT, int splits, bool f32,
-                     int path)
+                     int path, int NUM_CU)
 {
+    const double *const scale = g_cost_scale;
     const int64_t tiles = cdiv(M, t.BM) * cdiv(N, t.BN);
     const int64_t per = cdiv(KT, splits);
     const int64_t S = cdiv(KT, per);
@@ -142,35 +158,43 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
         const double floor = 1.2 / ((double)share * t.depth);
         if (slab < floor) slab = floor;
     }
+    slab *= scale[GEMM_COST_SLAB];
     const double t_mfma = rounds * ((double)per * slab + 1.0);
     const double esz = f32 ? 4.0 : 2.0;
     const double unique = ((double)M * K + (double)K * N) * esz + (double)M * N * 4.0;
     const double resident = (double)W < slots ? (double)W : slots;
     double hbm_rate = resident * 1.5 * (t.BM + t.BN) * 128.0 / 2.0;  // bytes/us the workgroups keep in flight
     if (hbm_rate > 4.5e6) hbm_rate = 4.5e6;
-    const double t_hbm = unique / hbm_rate;
-    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / 14.0e6;
-    double cost = 5.0 + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
-    if (S > 1) cost += 4.0 + (double)M * N * 4.0 * (double)(S + 1) / 3.0e6;
+    const double t_hbm = unique / (hbm_rate * scale[GEMM_COST_HBM]);
+    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / (14.0e6 * scale[GEMM_COST_L2]);
+    double cost = 5.0 * scale[GEMM_COST_FIXED] + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
+    if (S > 1) cost += 4.0 * scale[GEMM_COST_FIXED] + (double)M * N * 4.0 * (double)(S + 1) / (3.0e6 * scale[GEMM_COST_HBM]);
     return cost;
 }
 
-void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int &tile, int &splits)
+// max_ws_bytes: largest K-slice workspace the caller can provide (0 = no limit); automatic
+// picks that would need more are not considered.
+void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
+            int &tile, int &splits)
 {
     double best = 1e300;
     tile = g_forced_tile >= 0 ? g_forced_tile : 0;
     splits = 1;
+    // a forced slice count beyond the number of slabs means one slab per slice
+    const int forced = g_forced_splits > 0 ? (int)(g_forced_splits < KT ? g_forced_splits : KT) : 0;
     for (int t = 0; t < kNumTiles; ++t) {
         if (g_forced_tile >= 0 && t != g_forced_tile) continue;
         for (int s = 1; s <= 32; s *= 2) {
-            const int cand = g_forced_splits > 0 ? g_forced_splits : s;
+            const int cand = forced > 0 ? forced : s;
             if (cand > 1 && cand > KT) break;
-            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, path);
+            if (forced == 0 && cand > 1 && max_ws_bytes > 0 &&
+                (size_t)cand * (size_t)M * (size_t)N * sizeof(float) > max_ws_bytes)
+                break;
+            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, path, num_cu);
             if (c < best) { best = c; tile = t; splits = cand; }
-            if (g_forced_splits > 0) break;
+            if (forced > 0) break;
         }
     }
-    if (g_forced_splits > 0) splits = (int)(g_forced_splits < KT ? g_forced_splits : KT);
 }
 
 bool bad_matrix(const void *p, int layout, int64_t &ld, int64_t rows, int64_t cols)
@@ -183,27 +207,41 @@ bool bad_matrix(const void *p, int layout, int64_t &ld, int64_t rows, int64_t co
     return false;
 }
 
-int get_workspace(size_t bytes, void **out)
+// state of the current device (g_mutex held); asks the device for its CU count the first time
+int device_state(DeviceState **out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return GEMM_ERR_HIP;
-    std::lock_guard<std::mutex> lock(g_mutex);
-    Workspace &w = g_workspace[dev];
+    DeviceState &d = g_dev[dev];
+    if (d.num_cu == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = kDefaultNumCU;
+        d.num_cu = n;
+    }
+    *out = &d;
+    return GEMM_OK;
+}
+
+// workspace of (current device, stream), at least `bytes` long (g_mutex held)
+int get_workspace(DeviceState &d, hipStream_t stream, size_t bytes, void **out)
+{
+    Workspace &w = d.ws[stream];
     if (w.bytes < bytes) {
-        if (w.ptr) {
-            // earlier launches may still be reading the old buffer
-            if (hipDeviceSynchronize() != hipSuccess) return GEMM_ERR_HIP;
-            (void)hipFree(w.ptr);
-            w.ptr = nullptr;
-            w.bytes = 0;
-        }
+        const size_t want = bytes > 2 * w.bytes ? bytes : 2 * w.bytes;
         void *p = nullptr;
-        if (hipMalloc(&p, bytes) != hipSuccess) {
+        if (hipMalloc(&p, want) != hipSuccess) {
             (void)hipGetLastError();
-            return GEMM_ERR_WORKSPACE;
+            if (want == bytes || hipMalloc(&p, bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                return GEMM_ERR_WORKSPACE;
+            }
+            w.bytes = bytes;
+        } else {
+            w.bytes = want;
         }
+        if (w.ptr) d.retired.push_back(w.ptr);
         w.ptr = p;
-        w.bytes = bytes;
     }
     *out = w.ptr;
     return GEMM_OK;
@@ -246,8 +284,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     if (K == 0) {
         const int64_t total = M * N;
         const int blocks = (int)(cdiv(total, 256) < 65536 ? cdiv(total, 256) : 65536);
-        hipLaunchKernelGGL(fill_zero_kernel<TC>, dim3(blocks), dim3(256), 0, stream, C, ldc, (int)M, (int)N);
-        if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
+        if (launch_kernel(fill_zero_kernel<TC>, dim3(blocks), dim3(256), stream, C, ldc, (int)M, (int)N) != hipSuccess)
+            return GEMM_ERR_HIP;
         snprintf(t_last_config, sizeof t_last_config, "%s zero-fill", type_name);
         return GEMM_OK;
     }
@@ -266,12 +304,18 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
                                (uintptr_t)(ldb * (int64_t)sizeof(T));
     const int path = aligned ? 0 : ((low_bits & 3) != 0 ? 2 : 1);
 
+    // From here to the last launch under the lock: the selection reads the process-wide
+    // overrides, and a K-sliced call's two launches must reach the stream back to back (another
+    // host thread on the same stream would otherwise put its partials into the same workspace
+    // between them).  Launches are asynchronous, so the lock is held for microseconds.
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState *dev = nullptr;
+    if (device_state(&dev) != GEMM_OK) return GEMM_ERR_HIP;
+    const int num_cu = dev->num_cu;
+
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
-    {
-        std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, K, KT, f32, path, tile, splits);
-    }
+    choose(M, N, K, KT, f32, path, num_cu, 0, tile, splits);
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
     int64_t kt_per_split = cdiv(KT, splits);
@@ -293,23 +337,35 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.ld32 = ld32 ? 1 : 0;
     a.out16 = 0;
     a.stream_c = 0;
+    a.safe = g_forced_safe ? 1 : 0;
+    a.wide_c = 0;
     void *ws = nullptr;
     if (splits > 1) {
-        const int rc = get_workspace((size_t)splits * (size_t)M * (size_t)N * sizeof(float), &ws);
+        const size_t need = (size_t)splits * (size_t)M * (size_t)N * sizeof(float);
+        const int rc = get_workspace(*dev, stream, need, &ws);
         if (rc != GEMM_OK) return rc;
         a.C = (float *)ws;
         a.ldc = N;
         a.split_stride = M * N;
+        // slices are M*N floats from a 256-byte aligned base: rows are on 16-byte boundaries if N % 4 == 0
+        a.wide_c = (N % 4 == 0 && N < (1LL << 20) && g_store_mode != 1) ? 1 : 0;
     } else {
         a.C = (float *)C;
         a.ldc = ldc;
         a.split_stride = 0;
         a.out16 = out16 ? 1 : 0;
+        // C through LDS in whole rows (16 bytes per lane): always for binary16 C (the direct stores
+        // are 2 bytes per lane); for binary32 C when more than one round of tiles runs, where the
+        // fewer store instructions pay (8192^3 -1 %); a single round is over sooner with the
+        // stores leaving straight from the registers (2048^3 +4 %, 4096^3 binary32 +0.7 % staged)
+        const bool can_stage = (uintptr_t)C % 16 == 0 && (ldc * (int64_t)sizeof(TC)) % 16 == 0 && ldc < (1LL << 20);
+        const bool want_stage = out16 || tiles_m * tiles_n > (int64_t)num_cu * t.wg_per_cu;
+        a.wide_c = (can_stage && g_store_mode != 1 && (want_stage || g_store_mode == 2)) ? 1 : 0;
         // Non-temporal C stores (whole 128-byte lines only): measured 1-7 % faster when later rounds
         // of tiles are still reading A and B while C is written, or when C is small; 4-7 % slower
         // when one round of tiles writes more than the L2s hold in a single burst at the end.
         const bool lines = !out16 && ldc % 32 == 0 && (uintptr_t)C % 128 == 0;
-        const bool rounds = tiles_m * tiles_n > (int64_t)NUM_CU * t.wg_per_cu;
+        const bool rounds = tiles_m * tiles_n > (int64_t)num_cu * t.wg_per_cu;
         a.stream_c = (lines && (rounds || M * N * 4 <= (32LL << 20))) ? 1 : 0;
     }
     const dim3 grid((unsigned)(8 * cdiv(tiles_m * tiles_n * splits, 8)));
@@ -326,16 +382,15 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         const int blocks = (int)(cdiv(items, 256) < 4096 ? cdiv(items, 256) : 4096);
         // workspace slices are M * N floats each and the workspace is 256-byte aligned, so with
         // N % 4 == 0 every group of four columns is a 16-byte aligned piece of one row
-        if (N % 4 == 0)
-            hipLaunchKernelGGL((splitk_reduce_kernel<TC, 4>), dim3(blocks), dim3(256), 0, stream, (const float *)ws,
-                               (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
-        else
-            hipLaunchKernelGGL((splitk_reduce_kernel<TC, 1>), dim3(blocks), dim3(256), 0, stream, (const float *)ws,
-                               (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
-        if (hipGetLastError() != hipSuccess) return GEMM_ERR_HIP;
+        const hipError_t rc =
+            N % 4 == 0 ? launch_kernel(splitk_reduce_kernel<TC, 4>, dim3(blocks), dim3(256), stream, (const float *)ws,
+                                       (int64_t)(M * N), splits, C, ldc, (int)M, (int)N)
+                       : launch_kernel(splitk_reduce_kernel<TC, 1>, dim3(blocks), dim3(256), stream, (const float *)ws,
+                                       (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
+        if (rc != hipSuccess) return GEMM_ERR_HIP;
     }
-    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d", type_name, t.name,
-             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits);
+    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d%s", type_name, t.name,
+             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits, a.safe ? " safe" : "");
     return GEMM_OK;
 }
 
@@ -381,7 +436,7 @@ int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int align
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, K, KT, f32, aligned == 1 || aligned >= 16 ? 0 : (aligned == 2 ? 2 : 1), tile, splits);
+        choose(M, N, K, KT, f32, aligned == 1 || aligned >= 16 ? 0 : (aligned == 2 ? 2 : 1), kDefaultNumCU, 0, tile, splits);
     }
     const int64_t per = cdiv(KT, splits);
     splits = (int)cdiv(KT, per);  // no empty slices, as in the launch path
@@ -395,30 +450,53 @@ int gemm_force_config(const char *name)
     if (name == nullptr || strcmp(name, "auto") == 0 || name[0] == 0) {
         g_forced_tile = -1;
         g_forced_splits = 0;
+        g_forced_safe = false;
+        g_store_mode = 0;
         return GEMM_OK;
     }
+    // "<tile|auto>[:s<slices>][:safe][:direct|:staged]"
     std::string s(name);
-    int splits = 0;
-    const size_t colon = s.find(':');
-    if (colon != std::string::npos) {
+    int splits = 0, store_mode = 0;
+    bool safe = false;
+    size_t colon;
+    while ((colon = s.rfind(':')) != std::string::npos) {
         const std::string tail = s.substr(colon + 1);
-        if (tail.size() < 2 || tail[0] != 's') return GEMM_ERR_UNSUPPORTED;
-        char *end = nullptr;
-        const long v = strtol(tail.c_str() + 1, &end, 10);
-        if (*end != 0 || v < 1 || v > 1024) return GEMM_ERR_UNSUPPORTED;
-        splits = (int)v;
+        if (tail == "safe") {
+            safe = true;
+        } else if (tail == "direct" || tail == "staged") {
+            if (store_mode != 0) return GEMM_ERR_UNSUPPORTED;
+            store_mode = tail == "direct" ? 1 : 2;
+        } else {
+            if (tail.size() < 2 || tail[0] != 's' || splits != 0) return GEMM_ERR_UNSUPPORTED;
+            char *end = nullptr;
+            const long v = strtol(tail.c_str() + 1, &end, 10);
+            if (*end != 0 || v < 1 || v > 1024) return GEMM_ERR_UNSUPPORTED;
+            splits = (int)v;
+        }
         s = s.substr(0, colon);
     }
     int tile = -1;
-    if (s == "auto") {
-        tile = -1;
-    } else {
+    if (s != "auto") {
         for (int i = 0; i < kNumTiles; ++i)
             if (s == kTiles[i].name) tile = i;
         if (tile < 0) return GEMM_ERR_UNSUPPORTED;
     }
     g_forced_tile = tile;
     g_forced_splits = splits;
+    g_forced_safe = safe;
+    g_store_mode = store_mode;
+    return GEMM_OK;
+}
+
+int gemm_cost_model_scale(int term, double factor)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (term < 0) {
+        for (double &x : g_cost_scale) x = 1.0;
+        return GEMM_OK;
+    }
+    if (term >= GEMM_COST_TERMS || !(factor > 0.0)) return GEMM_ERR_INVALID_ARG;
+    g_cost_scale[term] = factor;
     return GEMM_OK;
 }
 
@@ -444,15 +522,21 @@ int gemm_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     int rc = GEMM_OK;
-    for (auto &kv : g_workspace) {
-        if (kv.second.ptr) {
-            int cur = 0;
-            (void)hipGetDevice(&cur);
-            if (hipSetDevice(kv.first) != hipSuccess || hipFree(kv.second.ptr) != hipSuccess) rc = GEMM_ERR_HIP;
-            (void)hipSetDevice(cur);
-        }
+    int cur = 0;
+    (void)hipGetDevice(&cur);
+    for (auto &kv : g_dev) {
+        DeviceState &d = kv.second;
+        if (d.ws.empty() && d.retired.empty()) continue;
+        if (hipSetDevice(kv.first) != hipSuccess) { rc = GEMM_ERR_HIP; continue; }
+        // hipFree waits for the work that may still use the buffer
+        for (auto &w : d.ws)
+            if (w.second.ptr && hipFree(w.second.ptr) != hipSuccess) rc = GEMM_ERR_HIP;
+        for (void *p : d.retired)
+            if (hipFree(p) != hipSuccess) rc = GEMM_ERR_HIP;
+        d.ws.clear();
+        d.retired.clear();
     }
-    g_workspace.clear();
+    (void)hipSetDevice(cur);
     return rc;
 }
 

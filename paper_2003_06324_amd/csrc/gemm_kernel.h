@@ -67,6 +67,8 @@ struct KernelArgs {
     int ld32;            // 256 * ld * sizeof(element) < 2^31 for A and B: tile-local byte offsets fit 32 bits
     int out16;           // C holds binary16: the accumulators are rounded (to nearest even) at the store
     int stream_c;        // binary32 C, no K-slices, rows of C start on 128-byte lines: stores may be non-temporal
+    int wide_c;          // C base and rows on 16-byte boundaries, ldc below 2^20: interior tiles store through LDS
+    int safe;            // every hand-over of an LDS buffer waits for all outstanding memory operations first
 };
 
 template <typename T> struct Elem;
@@ -84,6 +86,17 @@ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0
 // slabs stay in flight across it.  The "memory" clobber keeps the compiler from moving LDS
 // accesses over it; the waits that make the hand-over safe are issued by the caller.
 __device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_barrier" ::: "memory"); }
+
+// The "safe" variant of a hand-over (run-time switch): wait for every outstanding memory and
+// LDS operation of this wave, then a barrier.  The pipelines below hand buffers over with
+// counted waits and a single barrier per slab; the paper notes (Section 4.1) that removing
+// synchronisation is where races come from, so the same kernels can be run with every hand-over
+// fully synchronised to compare against.
+__device__ __forceinline__ void full_sync()
+{
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    barrier_keep_loads();
+}
 
 // Granule swizzle of a K-contiguous image.  A b128 fragment read has 16 consecutive lanes
 // on 16 consecutive rows at one logical granule; 16/GPR rows share a 256-byte bank period,
@@ -471,6 +484,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
 
     const T *A = (const T *)p.A;
     const T *B = (const T *)p.B;
+    const bool safe = p.safe != 0;
 
     float16_t acc[FM][FN];
 #pragma unroll
@@ -596,8 +610,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 if (h % 2 == 0) x_advance(h / 2 + 1 < n);
                 else y_advance(h / 2 + 1 < n);
             }
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NVA + NVB));  // tile 0 landed
-            barrier_keep_loads();
+            if (safe) {
+                full_sync();
+            } else {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(NVA + NVB));  // tile 0 landed
+                barrier_keep_loads();
+            }
 
             frag_t fa[2][FM], fb[2][FN];
             {
@@ -617,10 +635,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 x_advance(more);
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, no_load, L0());
                 // tile t+1 landed (all but the youngest NVX loads), own reads of tile t done
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVX));
-                barrier_keep_loads();
+                if (safe) {
+                    full_sync();
+                } else {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(NVX));
+                    barrier_keep_loads();
+                }
                 kgroup(fa[1], fb[1], fa[0], fb[0], nA, nB, 0, true, load_y, std::integral_constant<int, NVY>());
                 y_advance(more);
+                if (safe) full_sync();
             };
             // One steady-state tile whose slot pair starts at slot SA (compile time).
             auto tile_body = [&](auto sa_tag, const bool more) {
@@ -769,9 +792,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 kgroup(fa[1], fb[1], fa[0], fb[0], cA, cB, 2, true, no_load, L0());
                 kgroup(fa[0], fb[0], fa[1], fb[1], cA, cB, 3, true, store_set(set_tag), LAB());
                 // own LDS writes and reads done; the loads issued below stay in flight
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
-                barrier_keep_loads();
+                if (safe) {
+                    full_sync();
+                } else {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
+                    barrier_keep_loads();
+                }
                 kgroup(fa[1], fb[1], fa[0], fb[0], wA, wB, 0, true, fetch_set(set_tag), LAB());
+                if (safe) full_sync();
                 la.advance(sl + 2 + DEPTH < n);
                 lb.advance(sl + 2 + DEPTH < n);
                 cur ^= 1;
@@ -849,6 +877,71 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     // epilogue: accumulator register r of lane l holds
     //   row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 block
     float *C = p.C + (int64_t)slice * p.split_stride;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc does not know the buffer builtins
+    // Tiles that lie fully inside C, with rows of C on 16-byte boundaries (host flag): the store
+    // goes through LDS (the paper's epilogue via shared memory, Section 3.2 "Epilog" and
+    // Listing 5, with the operand buffers reused once they have drained), so that each lane
+    // writes 16 contiguous bytes of a row and a store instruction covers whole 128-byte lines:
+    // a quarter of the store instructions for binary32 C, an eighth for binary16 C.  Each wave
+    // stages its own sub-tile, one band of 32 rows at a time, in a private piece of LDS, as
+    // binary32 [32][TN + 8]: the 8 words of padding put the two rows a write instruction covers
+    // (four apart) into different halves of the 64 banks.  LDS operations of one wave execute in
+    // order, so the bands need no barrier between them.
+    if (p.wide_c && m0 + BM <= p.M && n0 + BN <= p.N) {
+        constexpr int SW = TN + 8;                 // staging row stride in words
+        constexpr int STAGE = 32 * SW * 4;         // bytes per wave
+        static_assert(NW * STAGE <= NBUF * SLOT, "staging area does not fit the operand buffers");
+        __syncthreads();  // every wave has read its last operands, every direct load has landed
+        GEMM_LDS(float) *stage = (GEMM_LDS(float) *)(lds + wave * STAGE);
+        const int lrow = 4 * (lane >> 5), lcol = lane & 31;
+        const int esz = p.out16 ? 2 : 4;
+        const int ldcb = (int)p.ldc * esz;
+        char *cbase = p.out16 ? (char *)((_Float16 *)p.C + (int64_t)m0 * p.ldc + n0)
+                              : (char *)(C + (int64_t)m0 * p.ldc + n0);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)cbase, 0, 0x7fffffff, 0x00020000);
+        auto band = [&](auto out16_tag, auto policy) {
+            constexpr bool O16 = decltype(out16_tag)::value;
+            constexpr int POLICY = decltype(policy)::value;
+            constexpr int WPL = O16 ? 8 : 4;          // staged words per lane and store (16 bytes of C)
+            constexpr int LPR = TN / WPL;             // lanes per row
+            constexpr int RPI = 64 / LPR;             // rows per store instruction
+            static_assert(64 % LPR == 0 && 32 % RPI == 0, "wave tile width not supported by the staged store");
+            const int srow = lane / LPR, spiece = lane % LPR;
+            const int voff = (wm * TM + srow) * ldcb + (wn * TN) * (O16 ? 2 : 4) + spiece * 16;
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        stage[(8 * (r >> 2) + (r & 3) + lrow) * SW + j * 32 + lcol] = acc[i][j][r];
+#pragma unroll
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const GEMM_LDS(float) *src = stage + (it * RPI + srow) * SW + spiece * WPL;
+                    const int soff = (i * 32 + it * RPI) * ldcb;
+                    if constexpr (O16) {
+                        const float4_t lo = *(const GEMM_LDS(float4_t) *)src;
+                        const float4_t hi = *(const GEMM_LDS(float4_t) *)(src + 4);
+                        half8_t h;
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            h[x] = (_Float16)lo[x];
+                            h[4 + x] = (_Float16)hi[x];
+                        }
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4_t, h), rsrc, voff, soff, POLICY);
+                    } else {
+                        const float4_t v = *(const GEMM_LDS(float4_t) *)src;
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4_t, v), rsrc, voff, soff, POLICY);
+                    }
+                }
+            }
+        };
+        if (p.out16) band(std::true_type(), std::integral_constant<int, 0>());
+        else if (p.stream_c) band(std::false_type(), std::integral_constant<int, 2>());
+        else band(std::false_type(), std::integral_constant<int, 0>());
+        return;
+    }
+#endif
     if (p.out16) {
         // binary16 result (never combined with K-slices: those reduce from binary32 partials)
         _Float16 *Ch = (_Float16 *)p.C;

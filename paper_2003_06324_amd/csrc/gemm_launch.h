@@ -3,17 +3,35 @@
 #pragma once
 #include "gemm_kernel.h"
 
+#include <tuple>
+#include <utility>
+
 namespace gemm_gfx950 {
+
+template <typename Tuple, size_t... I>
+static void fill_argv(void **argv, Tuple &vals, std::index_sequence<I...>)
+{
+    ((argv[I] = (void *)&std::get<I>(vals)), ...);
+}
+
+// Enqueues one kernel and returns the status of this launch alone (an error some earlier,
+// unrelated runtime call left pending in the calling thread is not picked up, unlike with
+// hipGetLastError after a <<<>>> launch).
+template <typename... Params, typename... Args>
+static hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t s, Args... args)
+{
+    std::tuple<Params...> vals(args...);
+    void *argv[sizeof...(Params)];
+    fill_argv(argv, vals, std::index_sequence_for<Params...>());
+    return hipLaunchKernel((const void *)kernel, grid, block, argv, 0, s);
+}
 
 template <typename T, int BM, int BN, int WM, int WN, bool AKC, bool BKC>
 static hipError_t launch_aligned(bool aligned, dim3 grid, hipStream_t s, const KernelArgs &a)
 {
     const dim3 block(WM * WN * 64);
-    if (aligned)
-        hipLaunchKernelGGL((gemm_tile_kernel<T, BM, BN, WM, WN, AKC, BKC, true>), grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL((gemm_tile_kernel<T, BM, BN, WM, WN, AKC, BKC, false>), grid, block, 0, s, a);
-    return hipGetLastError();
+    if (aligned) return launch_kernel(gemm_tile_kernel<T, BM, BN, WM, WN, AKC, BKC, true>, grid, block, s, a);
+    return launch_kernel(gemm_tile_kernel<T, BM, BN, WM, WN, AKC, BKC, false>, grid, block, s, a);
 }
 
 // akc: A is K-contiguous (row-major); bkc: B is K-contiguous (column-major)

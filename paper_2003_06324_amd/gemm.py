@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_cost_model_scale", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -52,6 +52,8 @@ def load_library():
         fn.restype = i32
     lib.gemm_force_config.argtypes = [ctypes.c_char_p]
     lib.gemm_force_config.restype = i32
+    lib.gemm_cost_model_scale.argtypes = [i32, ctypes.c_double]
+    lib.gemm_cost_model_scale.restype = i32
     lib.gemm_query_config.argtypes = [i32, i64, i64, i64, i32, ctypes.c_char_p, i32]
     lib.gemm_query_config.restype = i32
     lib.gemm_num_configs.argtypes = []
@@ -111,6 +113,15 @@ def gemm_bf16f32(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, str
     """C = A*B, bfloat16 operands (16-bit patterns), binary32 accumulation and result."""
     rc = load_library().gemm_bf16f32(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
                                      _ptr(C), layoutC, ldc, stream or None)
+    return _check(rc) if check else rc
+
+
+COST_SLAB, COST_HBM, COST_L2, COST_FIXED = 0, 1, 2, 3
+
+
+def cost_model_scale(term, factor=1.0, check=True):
+    """Multiply one term of the selection's cost model by factor; term < 0 resets all terms."""
+    rc = load_library().gemm_cost_model_scale(int(term), float(factor))
     return _check(rc) if check else rc
 
 

@@ -113,3 +113,41 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "single-GPU" in (r.stderr + r.stdout)
+
+
+def test_forced_slice_count_beyond_the_slab_count_still_costs_every_tile():
+    """A forced slice count larger than the number of K slabs means one slab per slice; the tile is
+    still chosen by cost (a tiny product must not land on the biggest tile unevaluated)."""
+    import paper_2003_06324_amd as g
+    try:
+        g.force_config("auto:s8")
+        for elem, K, slabs in ((2, 128, 2), (2, 64, 1), (4, 96, 3)):   # 64-k slabs (binary16), 32-k (binary32)
+            tile, slices = g.query_config(elem, 64, 64, K).split(":")
+            assert slices == "s%d" % slabs
+            assert not tile.startswith("t256"), tile   # a 64 x 64 product, costed: never the biggest tile
+        g.force_config("t128x128:s1024")
+        assert g.query_config(2, 512, 512, 640) == "t128x128:s10"
+    finally:
+        g.force_config(None)
+
+
+def test_force_config_suffixes():
+    import paper_2003_06324_amd as g
+    try:
+        for name in ("t64x64:safe", "t64x64:s2:safe", "auto:safe", "auto:s2:direct", "t128x128:direct:safe:s3", "t64x64:staged"):
+            assert g.force_config(name, check=False) == 0, name
+        for name in ("t64x64:s2:s3", "t64x64:fast", ":safe", "t64x64:s0", "auto:direct:staged"):
+            assert g.force_config(name, check=False) == -3, name
+    finally:
+        g.force_config(None)
+
+
+def test_cost_model_scale_arguments():
+    import paper_2003_06324_amd as g
+    try:
+        assert g.cost_model_scale(g.COST_SLAB, 1.1) == 0
+        assert g.cost_model_scale(7, 1.1, check=False) == -1
+        assert g.cost_model_scale(g.COST_HBM, 0.0, check=False) == -1
+        assert g.cost_model_scale(g.COST_HBM, -2.0, check=False) == -1
+    finally:
+        assert g.cost_model_scale(-1) == 0

@@ -188,3 +188,29 @@ def test_operand_beyond_4_gib(oracle):
         # exact column sums of the whole of C in int64
         col_sums = A.sum(axis=0, dtype=np.float64).astype(np.int64) @ B.astype(np.int64)   # |sums| < 2^53: exact
         assert np.array_equal(C.sum(axis=0, dtype=np.float64), col_sums.astype(np.float64)), cfg
+
+
+# ---------------------------------------------------------------------------
+# Every element at full size: one complete oracle product per case (tens of seconds on the
+# GPU machine's cores), compared with all of C at both bars.
+# ---------------------------------------------------------------------------
+def test_f16_8192_every_element_all_layouts(oracle, f16_8192):
+    A, B, _, _ = f16_8192
+    ref = oracle.gemm(8192, 8192, 8192, A, gi.ROW_MAJOR, B, gi.ROW_MAJOR, "f16")
+    for layout in ("NN", "NT", "TN", "TT"):
+        la, lb = gi.LAYOUTS[layout]
+        C = run_gpu("f16", A, B, la, lb)
+        check(C, ref, A, B, "f16", "f16 8192^3 %s, every element" % layout)
+
+
+def test_f32_4096_nt_every_element(oracle):
+    cfg, A, B, _, _ = gi.config_problem("f32_4096_nt")
+    ref = oracle.gemm(4096, 4096, 4096, A, gi.ROW_MAJOR, B, gi.ROW_MAJOR, "f32")
+    check(run_gpu("f32", A, B, gi.ROW_MAJOR, gi.COL_MAJOR), ref, A, B, "f32", "f32 4096^3 NT, every element")
+
+
+def test_f16_deep_k_every_element(oracle):
+    cfg, A, B, _, _ = gi.config_problem("f16_deep_k")
+    la, lb = gi.LAYOUTS[cfg["layout"]]
+    ref = oracle.gemm(cfg["M"], cfg["N"], cfg["K"], A, gi.ROW_MAJOR, B, gi.ROW_MAJOR, "f16")
+    check(run_gpu("f16", A, B, la, lb), ref, A, B, "f16", "f16 1024x1024x65536, every element")

@@ -1,0 +1,141 @@
+"""Behaviour around the kernels: K-sliced calls issued concurrently on several streams, a stale
+runtime error left by the caller, the fully synchronised ("safe") variant of every tile, and
+the two ways C is stored (staged through LDS in whole rows, or straight from registers)."""
+import ctypes
+import itertools
+
+import numpy as np
+import pytest
+
+import gemm_inputs as gi
+from gpu_util import run_gpu
+
+pytestmark = pytest.mark.gpu
+
+LAYS = (gi.ROW_MAJOR, gi.COL_MAJOR)
+LAYOUT_PAIRS = list(itertools.product(LAYS, repeat=2))
+
+
+def ref_of(oracle, A, B, dtype):
+    M, K = A.shape
+    return oracle.gemm(M, B.shape[1], K, A, gi.ROW_MAJOR, B, gi.ROW_MAJOR, dtype)
+
+
+def test_k_sliced_calls_on_two_streams_without_host_sync(oracle):
+    # Both streams run K-sliced products of different shapes, interleaved, with no host
+    # synchronisation in between: each (device, stream) pair has its own workspace, so the
+    # partial sums of one call can never land in the other's.  The larger product is issued
+    # first on each stream so that the second call of a stream finds a workspace big enough,
+    # the third round grows it again while the earlier launches are still queued.
+    import torch
+    import paper_2003_06324_amd as g
+    shapes = [(512, 384, 4096, 8), (192, 160, 1536, 4), (640, 512, 2048, 16)]
+    problems = []
+    for i, (M, N, K, s) in enumerate(shapes):
+        A, B = gi.make_problem(700 + i, M, N, K, "int", "f16")
+        problems.append((M, N, K, s, ref_of(oracle, A, B, "f16").astype(np.float32),
+                         torch.from_numpy(gi.store(A, gi.ROW_MAJOR).view(np.int16)).cuda(),
+                         torch.from_numpy(gi.store(B, gi.COL_MAJOR).view(np.int16)).cuda()))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    try:
+        for rep in range(3):
+            for si, s in enumerate(streams):
+                for pi in range(len(problems)):
+                    M, N, K, slices, ref, dA, dB = problems[(pi + si + rep) % len(problems)]
+                    with torch.cuda.stream(s):
+                        dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+                        g.force_config("t64x64:s%d" % slices)
+                        g.gemm_f16f32(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, s.cuda_stream)
+                        assert " s%d" % slices in g.last_config()
+                    outs.append((dC, ref, M, N))
+    finally:
+        g.force_config(None)
+    torch.cuda.synchronize()
+    for dC, ref, M, N in outs:
+        assert np.array_equal(dC.cpu().numpy().reshape(M, N), ref)
+
+
+def _hip_runtime():
+    """The HIP runtime this process already uses (the one torch loaded), by its mapped path."""
+    for line in open("/proc/self/maps"):
+        if "libamdhip64" in line:
+            return ctypes.CDLL(line.split()[-1])
+    raise RuntimeError("no HIP runtime mapped")
+
+
+def test_stale_runtime_error_of_the_caller_is_not_reported(oracle):
+    # An earlier failing runtime call of the caller (here: selecting a device that does not exist)
+    # leaves its error pending in the thread; the library must report its own launches only,
+    # also on the K-sliced path where a misread status would skip the reduce pass.
+    import torch
+    import paper_2003_06324_amd as g
+    M, N, K = 192, 160, 1536
+    A, B = gi.make_problem(41, M, N, K, "int", "f16")
+    ref = ref_of(oracle, A, B, "f16").astype(np.float32)
+    dA = torch.from_numpy(gi.store(A, gi.ROW_MAJOR).view(np.int16)).cuda()
+    dB = torch.from_numpy(gi.store(B, gi.COL_MAJOR).view(np.int16)).cuda()
+    stream = torch.cuda.current_stream().cuda_stream
+    hip = _hip_runtime()
+    try:
+        for force in ("t64x64:s1", "t64x64:s4"):
+            dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+            g.force_config(force)
+            torch.cuda.synchronize()
+            assert hip.hipSetDevice(ctypes.c_int(4096)) != 0   # fails, error stays pending
+            rc = g.gemm_f16f32(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, stream, check=False)
+            hip.hipGetLastError()                               # cleared before torch looks at it
+            assert rc == 0, (force, rc)
+            torch.cuda.synchronize()
+            assert np.array_equal(dC.cpu().numpy().reshape(M, N), ref), force
+    finally:
+        hip.hipGetLastError()
+        g.force_config(None)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_safe_variant_bit_exact_every_tile(oracle, dtype):
+    # the same kernels with every hand-over of an LDS buffer fully synchronised
+    import paper_2003_06324_amd as g
+    bk = 64 if dtype == "f16" else 32
+    for (M, N, K) in [(300, 260, 9 * bk), (257, 129, 3 * bk + 5)]:
+        A, B = gi.make_problem(17 + M, M, N, K, "int", dtype)
+        ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for tile in g.config_names():
+            for la, lb in LAYOUT_PAIRS:
+                for pads in ((0, 0, 0), (1, 3, 0)):   # direct-load and register-staged pipelines
+                    C, cfg = run_gpu(dtype, A, B, la, lb, pads=pads, force="%s:s1:safe" % tile, return_config=True)
+                    assert "safe" in cfg and tile in cfg
+                    assert np.array_equal(C, ref), (dtype, tile, M, N, K, la, lb, pads, cfg)
+    # and on data where the order of the additions shows: identical bits with and without
+    A, B = gi.make_problem(18, 512, 384, 1024, "normal", dtype)
+    for tile in g.config_names():
+        plain = run_gpu(dtype, A, B, gi.ROW_MAJOR, gi.COL_MAJOR, force=tile)
+        safe = run_gpu(dtype, A, B, gi.ROW_MAJOR, gi.COL_MAJOR, force=tile + ":safe")
+        assert np.array_equal(plain, safe), (dtype, tile)
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f32"), ("f16", "f16"), ("f32", "f32"), ("bf16", "f32")])
+def test_staged_and_direct_stores_agree(oracle, dtype, out):
+    # Interior tiles of a C whose rows start on 16-byte boundaries are staged through LDS and
+    # written 16 bytes per lane; ":direct" keeps the register-to-memory stores for the same tiles.
+    # Both must give the oracle's bits on integer data, with padded C rows, offset bases that are
+    # still 16-byte aligned, column-major C (operands swapped) and K slices.
+    import paper_2003_06324_amd as g
+    A, B = gi.make_problem(23, 600, 520, 200, "int", dtype)
+    if dtype == "bf16":
+        exact = oracle.gemm(600, 520, 200, gi.bfloat16_bits(A), 0, gi.bfloat16_bits(B), 0, "bf16")
+    else:
+        exact = oracle.gemm(600, 520, 200, A, 0, B, 0, dtype)
+    want = exact.astype(np.float32) if out == "f32" else oracle.round_to_half(exact)
+    step = 4 if out == "f32" else 8   # elements per 16 bytes of C
+    for tile in g.config_names():
+        for lc in LAYS:
+            for pads, offs in (((0, 0, 0), (0, 0, 0)), ((0, 0, step), (0, 0, 2 * step)), ((0, 0, 3), (0, 0, 0))):
+                for slices in (1, 2):
+                    for how in ("", ":direct", ":staged"):
+                        C, cfg = run_gpu(dtype, A, B, gi.ROW_MAJOR, gi.COL_MAJOR, lc, pads=pads, offsets=offs,
+                                         force="%s:s%d%s" % (tile, slices, how), return_config=True, out=out)
+                        assert np.array_equal(C.view(np.uint16 if out == "f16" else np.uint32),
+                                              want.view(np.uint16 if out == "f16" else np.uint32)), (cfg, lc, pads, offs, how)
