@@ -49,7 +49,7 @@
  *   be recorded into a HIP graph only once its stream's workspace has reached
  *   the size it needs, e.g. after the same call was made once outside the
  *   capture; calls that use no K-slices only launch kernels and can always be
- *   captured.
+ *   captured.  gemm_f16f32_noalloc never allocates.
  *
  * Sizes
  *   M, N, K >= 0 and each below 2^31 - 256.  M == 0 or N == 0: nothing is
@@ -123,6 +123,27 @@ int gemm_bf16f32(int64_t M, int64_t N, int64_t K,
                  const uint16_t *B, int layoutB, int64_t ldb,
                  float *C, int layoutC, int64_t ldc,
                  void *hip_stream);
+
+/*
+ * gemm_f16f32 for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments, layouts and errors as gemm_f16f32, but the call never
+ * calls hipMalloc or hipFree: the partial sums of a shape that is split along K
+ * go to a fixed array of GEMM_NOALLOC_SCRATCH_BYTES that every GPU the library
+ * runs on holds until the process ends.  The automatic selection only picks
+ * K-slice counts whose partials (slices * M * N * 4 bytes) fit the array; a
+ * forced configuration that needs more is refused with GEMM_ERR_WORKSPACE and
+ * nothing is enqueued.  All calls on one GPU share that GPU's array (its
+ * contents are whatever the last call left; every call overwrites what it
+ * reads), so calls that overlap in time on one GPU -- different streams, or
+ * graphs replayed concurrently -- race: order them.
+ */
+#define GEMM_NOALLOC_SCRATCH_BYTES (64u << 20)
+int gemm_f16f32_noalloc(int64_t M, int64_t N, int64_t K,
+                        const uint16_t *A, int layoutA, int64_t lda,
+                        const uint16_t *B, int layoutB, int64_t ldb,
+                        float *C, int layoutC, int64_t ldc,
+                        void *hip_stream);
 
 /*
  * Kernel-configuration control (the paper tunes the block tile per input size,

@@ -81,6 +81,11 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(TC *C, int64_t ldc, int 
 
 constexpr int kDefaultNumCU = 256;  // MI355X; the launch path asks the device (gemm_query_config uses this)
 
+// Partial results of the entry points that may not allocate (gemm_*_noalloc): one fixed array
+// per GPU, held until the process ends.  Host code never passes this name to a kernel: it is a
+// host-side stand-in; the device address comes from hipGetSymbolAddress (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[GEMM_NOALLOC_SCRATCH_BYTES];
+
 struct TileConfig {
     const char *name;
     int BM, BN;
@@ -121,6 +126,7 @@ double g_cost_scale[GEMM_COST_TERMS] = {1.0, 1.0, 1.0, 1.0};
 struct Workspace { void *ptr = nullptr; size_t bytes = 0; };
 struct DeviceState {
     int num_cu = 0;
+    void *static_scratch = nullptr;
     std::map<hipStream_t, Workspace> ws;
     std::vector<void *> retired;
 };
@@ -247,11 +253,27 @@ int get_workspace(DeviceState &d, hipStream_t stream, size_t bytes, void **out)
     return GEMM_OK;
 }
 
+// device address of this GPU's copy of `scratch` (g_mutex held); looked up once per device
+int static_scratch(DeviceState &d, void **out)
+{
+    if (d.static_scratch == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return GEMM_ERR_HIP;
+        }
+        d.static_scratch = ptr;
+    }
+    *out = d.static_scratch;
+    return GEMM_OK;
+}
+
 // T: operand type (bfloat16 runs the binary16 path with the other MFMA instruction, so it shares
-// the binary16 slab times of the selection); TC: element type of C (float, or _Float16 for gemm_f16f16)
+// the binary16 slab times of the selection); TC: element type of C (float, or _Float16 for gemm_f16f16).
+// noalloc: K-slice partials go to the fixed per-GPU array instead of a grown workspace.
 template <typename T, typename TC>
 int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t lda,
-              const void *B, int layB, int64_t ldb, TC *C, int layC, int64_t ldc, void *stream_)
+              const void *B, int layB, int64_t ldb, TC *C, int layC, int64_t ldc, void *stream_, bool noalloc = false)
 {
     constexpr bool f32 = sizeof(T) == 4;
     constexpr bool out16 = sizeof(TC) == 2;
@@ -315,7 +337,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
-    choose(M, N, K, KT, f32, path, num_cu, 0, tile, splits);
+    choose(M, N, K, KT, f32, path, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, tile, splits);
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
     int64_t kt_per_split = cdiv(KT, splits);
@@ -342,7 +364,14 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     void *ws = nullptr;
     if (splits > 1) {
         const size_t need = (size_t)splits * (size_t)M * (size_t)N * sizeof(float);
-        const int rc = get_workspace(*dev, stream, need, &ws);
+        int rc;
+        if (noalloc) {
+            // only a forced configuration can get here with more than the array holds
+            if (need > (size_t)GEMM_NOALLOC_SCRATCH_BYTES) return GEMM_ERR_WORKSPACE;
+            rc = static_scratch(*dev, &ws);
+        } else {
+            rc = get_workspace(*dev, stream, need, &ws);
+        }
         if (rc != GEMM_OK) return rc;
         a.C = (float *)ws;
         a.ldc = N;
@@ -389,8 +418,9 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
                                        (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
         if (rc != hipSuccess) return GEMM_ERR_HIP;
     }
-    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d%s", type_name, t.name,
-             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits, a.safe ? " safe" : "");
+    snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d%s%s", type_name, t.name,
+             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits, a.safe ? " safe" : "",
+             noalloc && splits > 1 ? " static-scratch" : "");
     return GEMM_OK;
 }
 
@@ -424,6 +454,13 @@ int gemm_bf16f32(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA
                  void *hip_stream)
 {
     return gemm_impl<__bf16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream);
+}
+
+int gemm_f16f32_noalloc(int64_t M, int64_t N, int64_t K, const uint16_t *A, int layoutA, int64_t lda,
+                        const uint16_t *B, int layoutB, int64_t ldb, float *C, int layoutC, int64_t ldc,
+                        void *hip_stream)
+{
+    return gemm_impl<_Float16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream, true);
 }
 
 int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen)

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_cost_model_scale", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -46,7 +46,7 @@ def load_library():
     lib = ctypes.CDLL(_LIB_PATH)
     i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
     sig = [i64, i64, i64, p, i32, i64, p, i32, i64, p, i32, i64, p]
-    for name in ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32"):
+    for name in ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc"):
         fn = getattr(lib, name)
         fn.argtypes = sig
         fn.restype = i32
@@ -116,6 +116,14 @@ def gemm_bf16f32(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, str
     return _check(rc) if check else rc
 
 
+def gemm_f16f32_noalloc(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stream=None, check=True):
+    """gemm_f16f32 that never allocates: K-slice partials go to the library's fixed per-GPU array."""
+    rc = load_library().gemm_f16f32_noalloc(M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb,
+                                            _ptr(C), layoutC, ldc, stream or None)
+    return _check(rc) if check else rc
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
 COST_SLAB, COST_HBM, COST_L2, COST_FIXED = 0, 1, 2, 3
 
 
