@@ -20,14 +20,29 @@ GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 2)
 GEMM_DECLARE_TILE(_Float16, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(_Float16, 128, 128, 2, 2)
 GEMM_DECLARE_TILE(_Float16, 64, 64, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 256, 128, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 128, 256, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 128, 64, 2, 2)
+GEMM_DECLARE_TILE(_Float16, 64, 128, 2, 2)
 GEMM_DECLARE_TILE(__bf16, 256, 256, 2, 2)
 GEMM_DECLARE_TILE(__bf16, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(__bf16, 128, 128, 2, 2)
 GEMM_DECLARE_TILE(__bf16, 64, 64, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 256, 128, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 128, 256, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 128, 64, 2, 2)
+GEMM_DECLARE_TILE(__bf16, 64, 128, 2, 2)
 GEMM_DECLARE_TILE(float, 256, 256, 2, 2)
 GEMM_DECLARE_TILE(float, 256, 256, 2, 4)
 GEMM_DECLARE_TILE(float, 128, 128, 2, 2)
 GEMM_DECLARE_TILE(float, 64, 64, 2, 2)
+GEMM_DECLARE_TILE(float, 256, 128, 2, 2)
+GEMM_DECLARE_TILE(float, 128, 256, 2, 2)
+GEMM_DECLARE_TILE(float, 128, 64, 2, 2)
+GEMM_DECLARE_TILE(float, 64, 128, 2, 2)
+GEMM_DECLARE_KSPLIT(_Float16, 64, 64)
+GEMM_DECLARE_KSPLIT(__bf16, 64, 64)
+GEMM_DECLARE_KSPLIT(float, 64, 64)
 }  // namespace gemm_gfx950
 
 namespace {
@@ -95,19 +110,34 @@ struct TileConfig {
     double general;             // slowdown of the register-staged (unaligned) path, 16-bit operands
     int depth;                  // slabs that path keeps in flight in registers
     launch_fn f16, f32, bf16;
+    int fallback;               // -1, or (K split across the waves of a workgroup) the tile that takes
+                                // operands this kernel does not serve: not 16-byte aligned, ragged K
+    int auto16, auto32;         // load paths (bit 0: direct loads, bit 1: register-staged, bit 2: register-staged on
+                                // 2-byte aligned operands) for which the automatic selection considers this
+                                // configuration, for 16-bit and for binary32 operands; 0: only when forced
 };
 
 // Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
 // under sustained MFMA load; these are not clock-peak figures).
+#define GEMM_TILE_LAUNCHERS(BM, BN, WM, WN) \
+    launch_tile<_Float16, BM, BN, WM, WN>, launch_tile<float, BM, BN, WM, WN>, launch_tile<__bf16, BM, BN, WM, WN>
+// Which configurations the automatic selection considers is a measured choice (sweep over the benchmark
+// shapes and the paper's size ranges): the rectangular tiles win only as 128x64 / 64x128 on mid-size
+// products whose operands are not 16-byte aligned (up to 9 %) and tie or lose elsewhere; splitting K
+// across the waves of a workgroup ties with the 2x2 arrangement of the same tile at 1024^3 and loses
+// 5-25 % elsewhere (four waves already occupy every SIMD of a CU here).  All of them can be forced.
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, 1, launch_tile<_Float16, 256, 256, 2, 2>, launch_tile<float, 256, 256, 2, 2>,
-     launch_tile<__bf16, 256, 256, 2, 2>},
-    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, 3, launch_tile<_Float16, 128, 128, 2, 2>, launch_tile<float, 128, 128, 2, 2>,
-     launch_tile<__bf16, 128, 128, 2, 2>},
-    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, 4, launch_tile<_Float16, 64, 64, 2, 2>, launch_tile<float, 64, 64, 2, 2>,
-     launch_tile<__bf16, 64, 64, 2, 2>},
-    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, 1, launch_tile<_Float16, 256, 256, 2, 4>, launch_tile<float, 256, 256, 2, 4>,
-     launch_tile<__bf16, 256, 256, 2, 4>},
+    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 2), -1, 7, 7},
+    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 128, 2, 2), -1, 7, 7},
+    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, 4, GEMM_TILE_LAUNCHERS(64, 64, 2, 2), -1, 7, 7},
+    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 4), -1, 7, 7},
+    {"t256x128", 256, 128, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(256, 128, 2, 2), -1, 0, 0},
+    {"t128x256", 128, 256, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(128, 256, 2, 2), -1, 0, 0},
+    {"t128x64", 128, 64, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 6, 0},
+    {"t64x128", 64, 128, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 6, 0},
+    // K split across the four waves of the workgroup (Section 5.3, small sizes)
+    {"k64x64", 64, 64, 4, 0.12, 0.65, 0.45, 1.9, 1.0, 1, launch_ksplit<_Float16, 64, 64>, launch_ksplit<float, 64, 64>,
+     launch_ksplit<__bf16, 64, 64>, 2, 0, 0},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -180,8 +210,9 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
 
 // max_ws_bytes: largest K-slice workspace the caller can provide (0 = no limit); automatic
 // picks that would need more are not considered.
+// ksplit_ok: the operands qualify for the kernels that split K across the waves of a workgroup
 void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
-            int &tile, int &splits)
+            bool ksplit_ok, int &tile, int &splits)
 {
     double best = 1e300;
     tile = g_forced_tile >= 0 ? g_forced_tile : 0;
@@ -190,6 +221,8 @@ void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int
     const int forced = g_forced_splits > 0 ? (int)(g_forced_splits < KT ? g_forced_splits : KT) : 0;
     for (int t = 0; t < kNumTiles; ++t) {
         if (g_forced_tile >= 0 && t != g_forced_tile) continue;
+        if (g_forced_tile < 0 && kTiles[t].fallback >= 0 && !ksplit_ok) continue;
+        if (g_forced_tile < 0 && !(((f32 ? kTiles[t].auto32 : kTiles[t].auto16) >> path) & 1)) continue;
         for (int s = 1; s <= 32; s *= 2) {
             const int cand = forced > 0 ? forced : s;
             if (cand > 1 && cand > KT) break;
@@ -337,7 +370,9 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
-    choose(M, N, K, KT, f32, path, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, tile, splits);
+    const bool ksplit_ok = aligned && K % BK == 0;
+    choose(M, N, K, KT, f32, path, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, ksplit_ok, tile, splits);
+    if (kTiles[tile].fallback >= 0 && !ksplit_ok) tile = kTiles[tile].fallback;  // forced, but not served by that kernel
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
     int64_t kt_per_split = cdiv(KT, splits);
@@ -360,7 +395,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.out16 = 0;
     a.stream_c = 0;
     a.safe = g_forced_safe ? 1 : 0;
-    a.wide_c = 0;
+    a.rows16_c = 0;
+    a.stage_c = 0;
     void *ws = nullptr;
     if (splits > 1) {
         const size_t need = (size_t)splits * (size_t)M * (size_t)N * sizeof(float);
@@ -377,7 +413,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         a.ldc = N;
         a.split_stride = M * N;
         // slices are M*N floats from a 256-byte aligned base: rows are on 16-byte boundaries if N % 4 == 0
-        a.wide_c = (N % 4 == 0 && N < (1LL << 20) && g_store_mode != 1) ? 1 : 0;
+        a.rows16_c = (N % 4 == 0 && N < (1LL << 20)) ? 1 : 0;
+        a.stage_c = (a.rows16_c && g_store_mode != 1) ? 1 : 0;
     } else {
         a.C = (float *)C;
         a.ldc = ldc;
@@ -389,7 +426,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         // stores leaving straight from the registers (2048^3 +4 %, 4096^3 binary32 +0.7 % staged)
         const bool can_stage = (uintptr_t)C % 16 == 0 && (ldc * (int64_t)sizeof(TC)) % 16 == 0 && ldc < (1LL << 20);
         const bool want_stage = out16 || tiles_m * tiles_n > (int64_t)num_cu * t.wg_per_cu;
-        a.wide_c = (can_stage && g_store_mode != 1 && (want_stage || g_store_mode == 2)) ? 1 : 0;
+        a.rows16_c = can_stage ? 1 : 0;
+        a.stage_c = (can_stage && g_store_mode != 1 && (want_stage || g_store_mode == 2)) ? 1 : 0;
         // Non-temporal C stores (whole 128-byte lines only): measured 1-7 % faster when later rounds
         // of tiles are still reading A and B while C is written, or when C is small; 4-7 % slower
         // when one round of tiles writes more than the L2s hold in a single burst at the end.
@@ -473,7 +511,8 @@ int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int align
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, K, KT, f32, aligned == 1 || aligned >= 16 ? 0 : (aligned == 2 ? 2 : 1), kDefaultNumCU, 0, tile, splits);
+        choose(M, N, K, KT, f32, aligned == 1 || aligned >= 16 ? 0 : (aligned == 2 ? 2 : 1), kDefaultNumCU, 0,
+               (aligned == 1 || aligned >= 16) && K % BK == 0, tile, splits);
     }
     const int64_t per = cdiv(KT, splits);
     splits = (int)cdiv(KT, per);  // no empty slices, as in the launch path

@@ -67,7 +67,8 @@ struct KernelArgs {
     int ld32;            // 256 * ld * sizeof(element) < 2^31 for A and B: tile-local byte offsets fit 32 bits
     int out16;           // C holds binary16: the accumulators are rounded (to nearest even) at the store
     int stream_c;        // binary32 C, no K-slices, rows of C start on 128-byte lines: stores may be non-temporal
-    int wide_c;          // C base and rows on 16-byte boundaries, ldc below 2^20: interior tiles store through LDS
+    int rows16_c;        // base and rows of C (or of the workspace) on 16-byte boundaries, ldc below 2^20
+    int stage_c;         // interior tiles store through LDS in whole rows (needs rows16_c)
     int safe;            // every hand-over of an LDS buffer waits for all outstanding memory operations first
 };
 
@@ -887,7 +888,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     // binary32 [32][TN + 8]: the 8 words of padding put the two rows a write instruction covers
     // (four apart) into different halves of the 64 banks.  LDS operations of one wave execute in
     // order, so the bands need no barrier between them.
-    if (p.wide_c && m0 + BM <= p.M && n0 + BN <= p.N) {
+    if (p.stage_c && m0 + BM <= p.M && n0 + BN <= p.N) {
         constexpr int SW = TN + 8;                 // staging row stride in words
         constexpr int STAGE = 32 * SW * 4;         // bytes per wave
         static_assert(NW * STAGE <= NBUF * SLOT, "staging area does not fit the operand buffers");

@@ -2,6 +2,7 @@
 // run-time (layout, alignment) choice onto the kernel template's booleans.
 #pragma once
 #include "gemm_kernel.h"
+#include "gemm_ksplit_kernel.h"
 
 #include <tuple>
 #include <utility>
@@ -44,11 +45,28 @@ hipError_t launch_tile(bool akc, bool bkc, bool aligned, dim3 grid, hipStream_t 
     return launch_aligned<T, BM, BN, WM, WN, false, false>(aligned, grid, s, a);
 }
 
+// K split across the waves of the workgroup; the caller passes 16-byte aligned operands and a K
+// that is a multiple of the slab (`aligned` is part of the common signature and always true here)
+template <typename T, int BM, int BN>
+hipError_t launch_ksplit(bool akc, bool bkc, bool aligned, dim3 grid, hipStream_t s, const KernelArgs &a)
+{
+    (void)aligned;
+    const dim3 block(256);
+    if (akc && bkc) return launch_kernel(gemm_ksplit_kernel<T, BM, BN, true, true>, grid, block, s, a);
+    if (akc && !bkc) return launch_kernel(gemm_ksplit_kernel<T, BM, BN, true, false>, grid, block, s, a);
+    if (!akc && bkc) return launch_kernel(gemm_ksplit_kernel<T, BM, BN, false, true>, grid, block, s, a);
+    return launch_kernel(gemm_ksplit_kernel<T, BM, BN, false, false>, grid, block, s, a);
+}
+
 typedef hipError_t (*launch_fn)(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
 
 #define GEMM_DECLARE_TILE(T, BM, BN, WM, WN) \
     extern template hipError_t launch_tile<T, BM, BN, WM, WN>(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
 #define GEMM_INSTANTIATE_TILE(T, BM, BN, WM, WN) \
     template hipError_t launch_tile<T, BM, BN, WM, WN>(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
+#define GEMM_DECLARE_KSPLIT(T, BM, BN) \
+    extern template hipError_t launch_ksplit<T, BM, BN>(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
+#define GEMM_INSTANTIATE_KSPLIT(T, BM, BN) \
+    template hipError_t launch_ksplit<T, BM, BN>(bool, bool, bool, dim3, hipStream_t, const KernelArgs &);
 
 }  // namespace gemm_gfx950

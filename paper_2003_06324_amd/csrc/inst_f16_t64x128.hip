@@ -1,0 +1,5 @@
+// Kernel instantiations: f16 operands, 64x128 workgroup tile, 2x2 waves.
+#include "gemm_launch.h"
+namespace gemm_gfx950 {
+GEMM_INSTANTIATE_TILE(_Float16, 64, 128, 2, 2)
+}

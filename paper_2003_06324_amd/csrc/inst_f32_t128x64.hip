@@ -1,0 +1,5 @@
+// Kernel instantiations: f32 operands, 128x64 workgroup tile, 2x2 waves.
+#include "gemm_launch.h"
+namespace gemm_gfx950 {
+GEMM_INSTANTIATE_TILE(float, 128, 64, 2, 2)
+}

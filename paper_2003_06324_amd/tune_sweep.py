@@ -7,6 +7,7 @@ calibrated on this output.
     python3 -m paper_2003_06324_amd.tune_sweep            # default shape list
     python3 -m paper_2003_06324_amd.tune_sweep f16 1536 1024 2048 NT
     python3 -m paper_2003_06324_amd.tune_sweep unaligned  # only the shapes with offset bases
+    python3 -m paper_2003_06324_amd.tune_sweep --all      # also print every forced configuration's time
 
 A shape may carry a byte offset added to both operand bases: operands that are not 16-byte
 aligned run the register-staged kernels, and 2-byte aligned ones a slower class of those.
@@ -40,6 +41,9 @@ def main():
     import gemm_inputs as gi
     import paper_2003_06324_amd as g
 
+    show_all = "--all" in sys.argv
+    if show_all:
+        sys.argv.remove("--all")
     shapes = DEFAULT_SHAPES + UNALIGNED_SHAPES
     if len(sys.argv) == 2 and sys.argv[1] == "unaligned":
         shapes = UNALIGNED_SHAPES
@@ -73,11 +77,15 @@ def main():
         pA, pB = A.data_ptr() + off, B.data_ptr() + off
         fn = lambda: call(M, N, K, pA, la, 0, pB, lb, 0, C, gi.ROW_MAJOR, 0, stream)
         results = []
+        g.force_config(None)
+        timed(fn, 20)   # bring the part to the shape's steady clock before the first forced configuration
         for tile in g.config_names():
             for s in (1, 2, 4, 8, 16, 32):
                 g.force_config("%s:s%d" % (tile, s))
                 results.append((timed(fn, 10), tile, s))
         results.sort()
+        if show_all:
+            print("   all: " + " ".join("%s:s%d=%.1f" % (t_, s_, us) for us, t_, s_ in results), flush=True)
         # the automatic choice and the best forced one again, back to back and in the same
         # thermal state (the first timings of a shape run on a cooler, faster part)
         g.force_config(None)

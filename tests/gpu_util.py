@@ -14,6 +14,19 @@ TOL = {"f32": 1e-6, "f16": 2e-4, "bf16": 2e-4}
 TIGHT = {"f32": 8 * 2.0 ** -24, "f16": 8 * 2.0 ** -24, "bf16": 8 * 2.0 ** -24}
 
 
+def all_tiles():
+    """Names of all kernel configurations of the built library (host call, no GPU needed)."""
+    import paper_2003_06324_amd as g
+    return g.config_names()
+
+
+def ran_tile(tile, cfg):
+    """The configuration string names the forced tile; a K-split-across-waves configuration
+    ("k64x64") hands operands it does not serve (not 16-byte aligned, K not a multiple of the
+    slab) to the two-dimensional tile of the same size ("t64x64")."""
+    return tile in cfg.split() or (tile[0] == "k" and "t" + tile[1:] in cfg.split())
+
+
 def to_device(buf):
     import torch
     if buf.dtype == np.float16:

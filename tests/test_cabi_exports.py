@@ -26,7 +26,7 @@ def test_host_only_entry_points():
     assert g.status_string(0) == "ok"
     assert "invalid" in g.status_string(-1)
     names = g.config_names()
-    assert names and all(n.startswith("t") for n in names)
+    assert names and all(n[0] in "tk" for n in names)   # 2-D tiles, K split across the waves
     for n in names:
         assert g.force_config(n) == 0
         assert g.force_config(n + ":s4") == 0
@@ -59,7 +59,11 @@ def test_selection_of_tile_and_k_slices():
     assert q(2, 8192, 128, 8192) == "t128x128:s4"
     assert q(2, 128, 8192, 8192) == "t128x128:s4"
     assert q(2, 4097, 3073, 1025, aligned=False) == "t256x256w8:s1"
-    assert q(2, 1000, 1500, 2000, aligned=False) == "t64x64:s1"
+    # mid-size products on the register-staged path: the 128x64 / 64x128 tiles (measured 2-9 % ahead of 64x64)
+    assert q(2, 1000, 1500, 2000, aligned=False) in ("t128x64:s1", "t64x128:s1")
+    assert q(2, 1536, 1024, 2048, aligned=8) in ("t128x64:s1", "t64x128:s1")
+    # ... and never for 16-byte aligned operands or binary32, where they tie or lose
+    assert q(2, 1536, 1024, 2048) == "t64x64:s1"
     assert q(4, 4096, 4096, 4096) == "t256x256:s1"
     # register-staged kernels (bases or leading dimensions not 16-byte aligned): the alignment
     # class is passed in bytes; mid-size shapes take the 128x128 tile, which keeps three slabs in

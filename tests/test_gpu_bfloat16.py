@@ -8,13 +8,13 @@ import numpy as np
 import pytest
 
 import gemm_inputs as gi
-from gpu_util import check, run_gpu
+from gpu_util import ran_tile, all_tiles, check, run_gpu
 
 pytestmark = pytest.mark.gpu
 
 LAYS = (gi.ROW_MAJOR, gi.COL_MAJOR)
 LAYOUT_PAIRS = list(itertools.product(LAYS, repeat=2))
-TILES = ["t256x256", "t256x256w8", "t128x128", "t64x64"]
+TILES = all_tiles()   # every configuration the library has, the K-split-across-waves ones included
 
 
 def reference(oracle, A, B):
@@ -44,7 +44,7 @@ def test_integer_inputs_bit_exact_every_tile(oracle, tile):
         for la, lb in LAYOUT_PAIRS:
             for splits in (1, 3):
                 C, cfg = run_gpu("bf16", A, B, la, lb, force="%s:s%d" % (tile, splits), return_config=True)
-                assert tile in cfg and cfg.startswith("bf16 ")
+                assert ran_tile(tile, cfg) and cfg.startswith("bf16 ")
                 assert np.array_equal(C.astype(np.float64), ref), (tile, M, N, K, la, lb, splits, cfg)
 
 

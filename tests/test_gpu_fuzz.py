@@ -5,11 +5,11 @@ import numpy as np
 import pytest
 
 import gemm_inputs as gi
-from gpu_util import run_gpu
+from gpu_util import all_tiles, run_gpu
 
 pytestmark = pytest.mark.gpu
 
-TILES = ["t256x256", "t256x256w8", "t128x128", "t64x64"]
+TILES = all_tiles()   # every configuration the library has, the K-split-across-waves ones included
 
 
 def draw_case(rng):

@@ -12,13 +12,13 @@ import numpy as np
 import pytest
 
 import gemm_inputs as gi
-from gpu_util import TIGHT, run_gpu
+from gpu_util import ran_tile, all_tiles, TIGHT, run_gpu
 
 pytestmark = pytest.mark.gpu
 
 LAYS = (gi.ROW_MAJOR, gi.COL_MAJOR)
 LAYOUT_PAIRS = list(itertools.product(LAYS, repeat=2))
-TILES = ["t256x256", "t256x256w8", "t128x128", "t64x64"]
+TILES = all_tiles()   # every configuration the library has, the K-split-across-waves ones included
 
 
 def half_step(x):
@@ -60,7 +60,7 @@ def test_integer_inputs_bit_exact_every_tile(oracle, tile):
         for la, lb in LAYOUT_PAIRS:
             for splits in (1, 3):
                 C, cfg = run_gpu("f16", A, B, la, lb, force="%s:s%d" % (tile, splits), return_config=True, out="f16")
-                assert tile in cfg and "f16f16" in cfg
+                assert ran_tile(tile, cfg) and "f16f16" in cfg
                 assert np.array_equal(C.view(np.uint16), ref.view(np.uint16)), (tile, M, N, K, la, lb, splits, cfg)
 
 

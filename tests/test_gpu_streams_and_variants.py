@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import gemm_inputs as gi
-from gpu_util import run_gpu
+from gpu_util import ran_tile, run_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -106,7 +106,7 @@ def test_safe_variant_bit_exact_every_tile(oracle, dtype):
             for la, lb in LAYOUT_PAIRS:
                 for pads in ((0, 0, 0), (1, 3, 0)):   # direct-load and register-staged pipelines
                     C, cfg = run_gpu(dtype, A, B, la, lb, pads=pads, force="%s:s1:safe" % tile, return_config=True)
-                    assert "safe" in cfg and tile in cfg
+                    assert "safe" in cfg and ran_tile(tile, cfg)
                     assert np.array_equal(C, ref), (dtype, tile, M, N, K, la, lb, pads, cfg)
     # and on data where the order of the additions shows: identical bits with and without
     A, B = gi.make_problem(18, 512, 384, 1024, "normal", dtype)
@@ -139,3 +139,50 @@ def test_staged_and_direct_stores_agree(oracle, dtype, out):
                                          force="%s:s%d%s" % (tile, slices, how), return_config=True, out=out)
                         assert np.array_equal(C.view(np.uint16 if out == "f16" else np.uint32),
                                               want.view(np.uint16 if out == "f16" else np.uint32)), (cfg, lc, pads, offs, how)
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f32"), ("f16", "f16"), ("f32", "f32"), ("bf16", "f32")])
+def test_k_split_across_the_waves_of_a_workgroup(oracle, dtype, out):
+    # The "k" configurations give each of the four waves the whole tile and one k-group of every
+    # slab, and sum the four partial tiles in LDS.  K is a multiple of the slab and the operands
+    # are 16-byte aligned here, so this kernel (not its two-dimensional stand-in) must run:
+    # every slab count from 1 to 7 and a long one, ragged M and N, all layouts, K-slices across
+    # workgroups on top, padded and column-major C, the fully synchronised variant.
+    import paper_2003_06324_amd as g
+    bk = 32 if dtype == "f32" else 64
+    ktiles = [t for t in g.config_names() if t[0] == "k"]
+    assert ktiles
+    for tile in ktiles:
+        for slabs in (1, 2, 3, 4, 5, 6, 7, 23):
+            K = slabs * bk
+            for (M, N) in ((136, 72), (64, 64), (200, 328)) if slabs in (1, 4, 23) else ((136, 72),):
+                A, B = gi.make_problem(51 + K + M, M, N, K, "int", dtype)
+                if dtype == "bf16":
+                    exact = oracle.gemm(M, N, K, gi.bfloat16_bits(A), 0, gi.bfloat16_bits(B), 0, "bf16")
+                else:
+                    exact = oracle.gemm(M, N, K, A, 0, B, 0, dtype)
+                want = exact.astype(np.float32) if out == "f32" else oracle.round_to_half(exact)
+                bits = np.uint16 if out == "f16" else np.uint32
+                for la, lb in LAYOUT_PAIRS:
+                    for force, lc, pads in ((tile, gi.ROW_MAJOR, (0, 0, 0)), (tile + ":s2", gi.ROW_MAJOR, (0, 0, 0)),
+                                            (tile + ":safe", gi.COL_MAJOR, (0, 0, 3)), (tile, gi.ROW_MAJOR, (8, 8, 8))):
+                        C, cfg = run_gpu(dtype, A, B, la, lb, lc, pads=pads, force=force, return_config=True, out=out)
+                        # M or N not a multiple of the 16-byte granule makes an M/N-contiguous operand
+                        # unaligned (granules straddle the edge): then the stand-in tile runs
+                        served = (la == gi.ROW_MAJOR or M % (16 // A.itemsize if dtype != "bf16" else 8) == 0) and \
+                                 (lb == gi.COL_MAJOR or N % (16 // B.itemsize if dtype != "bf16" else 8) == 0)
+                        assert (tile in cfg.split()) == served, (cfg, M, N, K, la, lb)
+                        assert np.array_equal(C.view(bits), want.view(bits)), (cfg, M, N, K, la, lb, lc, pads)
+    # random data: the bar of the other kernels
+    from gpu_util import check
+    if out == "f32":
+        A, B = gi.make_problem(52, 320, 192, 20 * bk, "normal", dtype)
+        if dtype == "bf16":
+            ref = oracle.gemm(320, 192, 20 * bk, gi.bfloat16_bits(A), 0, gi.bfloat16_bits(B), 0, "bf16")
+        else:
+            ref = oracle.gemm(320, 192, 20 * bk, A, 0, B, 0, dtype)
+        for tile in ktiles:
+            for la, lb in LAYOUT_PAIRS:
+                C, cfg = run_gpu(dtype, A, B, la, lb, force=tile, return_config=True)
+                assert tile in cfg.split()
+                check(C, ref, A, B, dtype, cfg)
