@@ -191,6 +191,19 @@ int gemm_cost_model_scale(int term, double factor);
  */
 int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen);
 
+/*
+ * Profiling aid (the paper times whole kernels, Section 5; this shows where inside a
+ * launch the time goes).  With a device buffer of 8 * workgroups 64-bit words set, the first
+ * thread of every workgroup of the following gemm_* launches records a constant-rate 100 MHz
+ * clock at the phase boundaries of its tile: word 0 start, 1 first operands landed (direct-load
+ * kernels only), 2 K loop done, 3 shared memory free for the epilogue, 4 stores issued,
+ * 5 stores complete; word 7 says where it ran (XCC id in the upper half, the hardware id
+ * register in the lower).  Workgroups numbered beyond the buffer record nothing; a later
+ * launch overwrites an earlier one's records.  NULL switches it off (the default).  The
+ * caller owns the buffer and keeps it alive while set.  Process-wide.
+ */
+int gemm_set_phase_trace(void *device_buffer, int64_t workgroups);
+
 /* Number of tile configurations, and the name of the i-th (NULL if out of range). */
 int gemm_num_configs(void);
 const char *gemm_config_name(int i);

@@ -147,6 +147,8 @@ int g_forced_splits = 0;   // 0: heuristic
 bool g_forced_safe = false;
 int g_store_mode = 0;  // 0: by shape; 1: ":direct", C straight from registers; 2: ":staged", through LDS where possible
 double g_cost_scale[GEMM_COST_TERMS] = {1.0, 1.0, 1.0, 1.0};
+unsigned long long *g_trace = nullptr;  // profiling aid (gemm_set_phase_trace)
+int64_t g_trace_records = 0;
 
 // K-slice workspaces: one per (device, stream).  Work on one stream is ordered, so a stream's
 // buffer is never used by two launches at once; different streams never share one.  A buffer
@@ -397,6 +399,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.safe = g_forced_safe ? 1 : 0;
     a.rows16_c = 0;
     a.stage_c = 0;
+    a.trace = g_trace;
+    a.trace_records = (int)(g_trace_records < (1LL << 30) ? g_trace_records : (1LL << 30));
     void *ws = nullptr;
     if (splits > 1) {
         const size_t need = (size_t)splits * (size_t)M * (size_t)N * sizeof(float);
@@ -561,6 +565,15 @@ int gemm_force_config(const char *name)
     g_forced_splits = splits;
     g_forced_safe = safe;
     g_store_mode = store_mode;
+    return GEMM_OK;
+}
+
+int gemm_set_phase_trace(void *device_buffer, int64_t workgroups)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (device_buffer != nullptr && workgroups <= 0) return GEMM_ERR_INVALID_ARG;
+    g_trace = (unsigned long long *)device_buffer;
+    g_trace_records = device_buffer ? workgroups : 0;
     return GEMM_OK;
 }
 

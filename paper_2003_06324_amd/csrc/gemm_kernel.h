@@ -70,7 +70,27 @@ struct KernelArgs {
     int rows16_c;        // base and rows of C (or of the workspace) on 16-byte boundaries, ldc below 2^20
     int stage_c;         // interior tiles store through LDS in whole rows (needs rows16_c)
     int safe;            // every hand-over of an LDS buffer waits for all outstanding memory operations first
+    unsigned long long *trace;  // profiling aid, normally null: 8 words per workgroup (see trace_mark)
+    int trace_records;          // workgroups the trace buffer has room for
 };
+
+// Profiling aid: with a trace buffer set, thread 0 of every workgroup records the constant-rate
+// (100 MHz) clock at the phase boundaries of its tile - 0 start, 1 first slab landed, 2 K loop
+// done, 3 LDS free for the epilogue, 4 stores issued, 5 stores complete - and in word 7 where it
+// ran (XCC id above bit 32, the hardware id register below).  Costs a scalar branch per mark.
+__device__ __forceinline__ void trace_mark(const KernelArgs &p, int slot)
+{
+    if (p.trace != nullptr && threadIdx.x == 0 && (int)blockIdx.x < p.trace_records)
+        p.trace[(size_t)blockIdx.x * 8 + slot] = wall_clock64();
+}
+__device__ __forceinline__ void trace_place(const KernelArgs &p)
+{
+    if (p.trace != nullptr && threadIdx.x == 0 && (int)blockIdx.x < p.trace_records) {
+        const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID: wave, SIMD, CU, SH, SE ...
+        const unsigned xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20);  // XCC_ID
+        p.trace[(size_t)blockIdx.x * 8 + 7] = ((unsigned long long)xcc << 32) | hw;
+    }
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<_Float16> { static constexpr int EPC = 8, KG = 16, BK = KG * KGS; };
@@ -465,6 +485,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
     const int per_xcd = (nwork + 7) >> 3;
     const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (work >= nwork) return;
+    trace_mark(p, 0);
+    trace_place(p);
     const int slice = work / ntiles;
     const int lin = work - slice * ntiles;
     constexpr int GM = 8;
@@ -618,6 +640,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 barrier_keep_loads();
             }
 
+            trace_mark(p, 1);
             frag_t fa[2][FM], fb[2][FN];
             {
                 const GEMM_LDS(char) *cA = lds + PA * SLOT, *cB = lds + PB * SLOT;
@@ -875,6 +898,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         }
     }
 
+    trace_mark(p, 2);
+    // marks 4 and 5 of the profiling trace: all stores of this thread issued / complete
+    auto trace_stores = [&]() {
+        if (p.trace != nullptr) {
+            trace_mark(p, 4);
+            __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+            trace_mark(p, 5);
+        }
+    };
     // epilogue: accumulator register r of lane l holds
     //   row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 block
     float *C = p.C + (int64_t)slice * p.split_stride;
@@ -893,6 +925,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         constexpr int STAGE = 32 * SW * 4;         // bytes per wave
         static_assert(NW * STAGE <= NBUF * SLOT, "staging area does not fit the operand buffers");
         __syncthreads();  // every wave has read its last operands, every direct load has landed
+        trace_mark(p, 3);
         GEMM_LDS(float) *stage = (GEMM_LDS(float) *)(lds + wave * STAGE);
         const int lrow = 4 * (lane >> 5), lcol = lane & 31;
         const int esz = p.out16 ? 2 : 4;
@@ -940,9 +973,11 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         if (p.out16) band(std::true_type(), std::integral_constant<int, 0>());
         else if (p.stream_c) band(std::false_type(), std::integral_constant<int, 2>());
         else band(std::false_type(), std::integral_constant<int, 0>());
+        trace_stores();
         return;
     }
 #endif
+    trace_mark(p, 3);
     if (p.out16) {
         // binary16 result (never combined with K-slices: those reduce from binary32 partials)
         _Float16 *Ch = (_Float16 *)p.C;
@@ -969,6 +1004,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                         __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, h), rsrc, voffj[j] + roff, 0, 0);
                     }
                 }
+            trace_stores();
             return;
         }
 #endif
@@ -984,6 +1020,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                 }
             }
         }
+        trace_stores();
         return;
     }
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of hipcc does not know the buffer builtins
@@ -1019,6 +1056,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         };
         if (p.stream_c) store_all(std::integral_constant<int, 2>());
         else store_all(std::integral_constant<int, 0>());
+        trace_stores();
         return;
     }
     // Edge tiles, same descriptor trick: the descriptor's range ends with the last valid row
@@ -1046,6 +1084,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc, voffj[j] + roff, 0, 0);
                 }
             }
+        trace_stores();
         return;
     }
 #endif
@@ -1061,6 +1100,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
             }
         }
     }
+    trace_stores();
 }
 
 }  // namespace gemm_gfx950

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -52,6 +52,8 @@ def load_library():
         fn.restype = i32
     lib.gemm_force_config.argtypes = [ctypes.c_char_p]
     lib.gemm_force_config.restype = i32
+    lib.gemm_set_phase_trace.argtypes = [p, i64]
+    lib.gemm_set_phase_trace.restype = i32
     lib.gemm_cost_model_scale.argtypes = [i32, ctypes.c_double]
     lib.gemm_cost_model_scale.restype = i32
     lib.gemm_query_config.argtypes = [i32, i64, i64, i64, i32, ctypes.c_char_p, i32]
@@ -131,6 +133,12 @@ def cost_model_scale(term, factor=1.0, check=True):
     """Multiply one term of the selection's cost model by factor; term < 0 resets all terms."""
     rc = load_library().gemm_cost_model_scale(int(term), float(factor))
     return _check(rc) if check else rc
+
+
+def set_phase_trace(buffer=None, workgroups=0):
+    """Device buffer of 8 * workgroups uint64 that the kernels fill with per-workgroup phase
+    timestamps (see include/gemm.h); None switches the trace off."""
+    return _check(load_library().gemm_set_phase_trace(_ptr(buffer), int(workgroups)))
 
 
 def query_config(elem_bytes, M, N, K, aligned=True):

@@ -10,6 +10,13 @@ per launch: the part holds a power limit by lowering its clock, which is what bo
 random-data figures.
 
     python3 -m paper_2003_06324_amd.profile_workload --size 8192 --layout NT --dist normal --sustain 4
+
+With --phases it switches on the library's per-workgroup phase trace (gemm_set_phase_trace), runs
+the launch a few times and prints, from the last launch, how long the workgroups spend in each
+phase of a tile (start-up, K loop, hand-over of shared memory, stores) and how long a CU waits
+between two workgroups: where the time that is not matrix-core time goes.
+
+    python3 -m paper_2003_06324_amd.profile_workload --size 8192 --layout NT --dist normal --phases
 """
 import argparse
 import os
@@ -28,6 +35,7 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0, help="also run a copy kernel of this many MiB")
     ap.add_argument("--force", default=None, help="tile configuration override, e.g. t256x256")
     ap.add_argument("--sustain", type=float, default=0.0, help="seconds of back-to-back launches with power sampling")
+    ap.add_argument("--phases", action="store_true", help="per-workgroup phase trace of the last launch")
     args = ap.parse_args()
 
     import torch
@@ -56,6 +64,10 @@ def main():
                 2.0 * M * N * K, "%s %dx%dx%d %s %s" % (args.dtype, M, N, K, args.layout, args.dist))
         print("gemm:", g.last_config())
         return
+    if args.phases:
+        phases(lambda: fn(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream), max(args.iters, 20),
+               "%s %dx%dx%d %s %s" % (args.dtype, M, N, K, args.layout, args.dist))
+        return
     for _ in range(args.iters):
         fn(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
     torch.cuda.synchronize()
@@ -68,6 +80,52 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print("copy: %d MiB read + %d MiB written, x3" % (args.copy_mib, args.copy_mib))
+
+
+def phases(launch, iters, what):
+    """Phase table of the last of `iters` launches from the library's per-workgroup trace."""
+    import numpy as np
+    import torch
+    import paper_2003_06324_amd as g
+    cap = 1 << 16
+    buf = torch.zeros(cap * 8, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    g.set_phase_trace(buf, cap)
+    try:
+        for _ in range(iters):
+            launch()
+        torch.cuda.synchronize()
+    finally:
+        g.set_phase_trace(None)
+    rec = buf.cpu().numpy().reshape(cap, 8)
+    rec = rec[rec[:, 0] != 0]
+    ts = (rec[:, :6] - rec[:, 0].min()) * 0.01          # microseconds (100 MHz clock)
+    print("%s [%s]: %d workgroups, span of the launch %.1f us" % (what, g.last_config(), len(rec), ts[:, 5].max()))
+    have_first = bool((rec[:, 1] != 0).all())     # only the direct-load kernels record it
+    spans = ([("start -> first operands landed", 0, 1), ("K loop", 1, 2)] if have_first
+             else [("start -> K loop done", 0, 2)])
+    spans += [("shared memory handed to the epilogue", 2, 3), ("stores issued", 3, 4), ("stores complete", 4, 5)]
+    for name, i0, i1 in spans:
+        d = ts[:, i1] - ts[:, i0]
+        print("  %-38s mean %7.2f us   p10 %7.2f   p50 %7.2f   p90 %7.2f   max %7.2f" % (
+            name, d.mean(), np.percentile(d, 10), np.percentile(d, 50), np.percentile(d, 90), d.max()))
+    hw, xcc = rec[:, 7] & 0xFFFFFFFF, rec[:, 7] >> 32
+    cu = ((xcc & 0xF) << 12) | (((hw >> 13) & 7) << 8) | (((hw >> 12) & 1) << 4) | ((hw >> 8) & 0xF)
+    gaps, per_cu = [], []
+    for c in np.unique(cu):
+        idx = np.where(cu == c)[0]
+        idx = idx[np.argsort(ts[idx, 0])]
+        per_cu.append(len(idx))
+        gaps += [ts[b, 0] - ts[a, 5] for a, b in zip(idx[:-1], idx[1:])]
+    print("  %d CUs used, %d..%d workgroups each" % (len(per_cu), min(per_cu), max(per_cu)))
+    if gaps:
+        gaps = np.array(gaps)
+        print("  %-38s mean %7.2f us   p50 %7.2f   p90 %7.2f   max %7.2f" % (
+            "CU idle between two workgroups", gaps.mean(), np.percentile(gaps, 50), np.percentile(gaps, 90), gaps.max()))
+    total = ts[:, 5] - ts[:, 0]
+    loop = ts[:, 2] - ts[:, 1 if have_first else 0]
+    print("  per workgroup: %.2f us in all, %.2f us (%.1f %%) outside the K loop" % (
+        total.mean(), (total - loop).mean(), 100.0 * (total - loop).mean() / total.mean()))
 
 
 def sustain(launch, seconds, flop, what):
