@@ -4,6 +4,13 @@ A step is one pass over the headline workload: the FP16-in / FP32-accumulate
 8192^3 product in all four operand layouts (NN, NT, TN, TT; N = row-major
 operand, T = column-major operand), i.e. four library calls.  Inputs are
 seeded synthetic matrices already resident in HBM.  Prints one JSON line.
+
+Beside the headline it carries, outside the timed step: `configs`, one row per benchmark
+configuration (kernel chosen, median / minimum microseconds per launch from HIP events, TFLOP/s,
+the MFMA and HBM floors and the fraction of the binding one); `counters`, the rocprofv3 figures of
+the dominant headline launch read from profiles/counters.json (MfmaUtil, LDS bank-conflict ratio,
+HBM bytes, turned into GB/s with the launch time measured here); the zero-data, binary16-output
+and bfloat16 context runs; and the CPU oracle's rate on a bounded sample.
 """
 import argparse
 import json
@@ -52,6 +59,61 @@ def time_calls(fn, calls, steps, warmup):
     return wall, per_call
 
 
+def config_rows(per_layout, S, skip_big):
+    """One row per benchmark configuration.  The four headline launches are taken from the timed
+    step; the others are timed here, each on its own seeded operands (generated on the host
+    exactly as the parity tests generate them); median and minimum over batches of back-to-back launches."""
+    import numpy as np
+    import torch
+    import gemm_inputs as gi
+    import paper_2003_06324_amd as g
+    rows = []
+    stream = torch.cuda.current_stream()
+    for name, cfg in gi.CONFIGS.items():
+        M, N, K, lay, dt = cfg["M"], cfg["N"], cfg["K"], cfg["layout"], cfg["dtype"]
+        esz = 4 if dt == "f32" else 2
+        flop = 2.0 * M * N * K
+        algo = (M * K + K * N) * esz + M * N * 4
+        mfma_us = flop / (PEAK_TFLOPS[dt] * 1e12) * 1e6
+        hbm_us = algo / 8e12 * 1e6
+        if name.startswith("f16_8192_") and S == 8192:
+            pl = per_layout[lay]
+            med, mn, kernel = pl["ms_median"] * 1e3, pl["ms_min"] * 1e3, pl["kernel"]
+        else:
+            if skip_big and M * K + K * N > (1 << 27):
+                continue
+            _, A_np, B_np, bufA, bufB = gi.config_problem(name)
+            if dt == "f16":
+                bufA, bufB = bufA.view(np.int16), bufB.view(np.int16)
+            dA, dB = torch.from_numpy(bufA).cuda(), torch.from_numpy(bufB).cuda()
+            C = torch.empty(M * N, dtype=torch.float32, device="cuda")
+            la, lb = gi.LAYOUTS[lay]
+            fn = g.gemm_f32 if dt == "f32" else g.gemm_f16f32
+            call = (M, N, K, dA, la, 0, dB, lb, 0, C, gi.ROW_MAJOR, 0)
+            # back-to-back launches between two events, as the tuning sweep times them (an event after
+            # every launch would add a few microseconds of its own to the small shapes); seven batches
+            iters = 20 if flop > 5e10 else 100
+            for _ in range(20):
+                fn(*call, stream.cuda_stream)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(8)]
+            torch.cuda.synchronize()
+            ev[0].record(stream)
+            for b in range(7):
+                for _ in range(iters):
+                    fn(*call, stream.cuda_stream)
+                ev[b + 1].record(stream)
+            torch.cuda.synchronize()
+            us = sorted(ev[b].elapsed_time(ev[b + 1]) * 1e3 / iters for b in range(7))
+            med, mn, kernel = us[len(us) // 2], us[0], g.last_config()
+            del dA, dB, C
+        floor = max(mfma_us, hbm_us)
+        rows.append({"config": name, "shape": [M, N, K], "layout": lay, "dtype": dt, "kernel": kernel,
+                     "us_median": round(med, 2), "us_min": round(mn, 2), "tflops": round(flop / med / 1e6, 1),
+                     "floor_mfma_us": round(mfma_us, 2), "floor_hbm_us": round(hbm_us, 2),
+                     "bound": "mfma" if mfma_us >= hbm_us else "hbm", "frac_of_floor": round(floor / med, 4)})
+    return rows
+
+
 def cpu_baseline(A_np, B_np, gpu_rows, target_seconds=15.0):
     """Oracle timed on the host cores on the first rows of the NT case; also returns the
     largest deviation of the GPU result on those rows (stated metric)."""
@@ -90,6 +152,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration rows (they launch other kernels)")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the zero-data and binary16-output context runs (they launch the headline kernels "
                          "on other data, which would mix into per-kernel averages of a profiler)")
@@ -135,13 +198,21 @@ def main():
     # dominant kernel = the layout that takes the largest share of the step
     dom = max(names, key=lambda n: per_layout[n]["ms"])
     achieved = flop / per_layout[dom]["ms"] / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    traffic, counters = None, None
+    cpath = os.path.join(ROOT, "profiles", "counters.json")
+    if os.path.exists(cpath):
         try:
-            traffic = json.load(open(tpath)).get("f16_%d_%s" % (S, dom))
+            c = json.load(open(cpath)).get("f16_%d_%s" % (S, dom))
+            if c:
+                traffic = c["hbm_bytes"]
+                counters = {"case": "f16_%d_%s" % (S, dom), "mfma_util": c["mfma_util"],
+                            "lds_bank_conflict_ratio": c["lds_bank_conflict_ratio"],
+                            "hbm_bytes_per_launch": c["hbm_bytes"], "algorithmic_bytes_per_launch": c["algorithmic_bytes"],
+                            "hbm_gbps": round(c["hbm_bytes"] / (per_layout[dom]["ms"] * 1e-3) / 1e9, 1),
+                            "source": "profiles/counters.json <- profiles/benchmark_configs_pmc_counters.txt (rocprofv3 --pmc, "
+                                      "separate runs); GB/s uses the launch time measured in this run"}
         except Exception:
-            traffic = None
+            traffic, counters = None, None
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_TFLOPS["f16"], 4), "traffic": traffic,
                 "kernel": per_layout[dom]["kernel"], "flop_per_launch": flop,
@@ -205,6 +276,10 @@ def main():
         "pct_of_peak": round(100.0 * value / PEAK_TFLOPS["f16"], 2),
         "per_layout": per_layout, "roofline": roofline, "fp32": fp32,
     }
+    if counters is not None:
+        out["counters"] = counters
+    if not args.no_configs:
+        out["configs"] = config_rows(per_layout, S, skip_big=False)
     if zero_data is not None:
         out["zero_data"], out["fp16_out"], out["bf16"] = zero_data, fp16_out, bf16
     if not args.no_cpu_baseline:

@@ -155,3 +155,44 @@ def test_cost_model_scale_arguments():
         assert g.cost_model_scale(g.COST_HBM, -2.0, check=False) == -1
     finally:
         assert g.cost_model_scale(-1) == 0
+
+
+def test_selection_is_stable_under_ten_percent_changes_of_the_cost_model():
+    """The cost model's constants were measured on one part and boxes differ by several percent:
+    scaling any of its four terms by 0.9 or 1.1 must not change the pick on the shapes of the
+    tuning sweep (benchmark configurations, the paper's size ranges, offset operand bases).
+    One shape is known to sit on a boundary and is listed instead: 1536x1024x2048 on aligned
+    operands moves from the 64x64 to the 128x128 tile (measured 19 % slower) when slab times or
+    the L2 rate are taken 10 % lower."""
+    import paper_2003_06324_amd as g
+    from paper_2003_06324_amd.tune_sweep import DEFAULT_SHAPES, UNALIGNED_SHAPES
+
+    def picks():
+        out = {}
+        for sh in DEFAULT_SHAPES + UNALIGNED_SHAPES:
+            dt, M, N, K = sh[:4]
+            off = sh[5] if len(sh) > 5 else 0
+            align = 16 if off == 0 else (2 if off % 4 else (4 if off % 8 else 8))
+            if (M, N, K) == (1000, 1500, 2000):
+                align = 8      # leading dimension 1500 halves = 3000 bytes
+            if (M, N, K) == (4097, 3073, 1025):
+                align = 2      # leading dimensions 1025 and 3073 halves
+            out[sh] = g.query_config(4 if dt == "f32" else 2, M, N, K, align)
+        return out
+
+    known = {("f16", 1536, 1024, 2048, "NT"): {(g.COST_SLAB, 0.9), (g.COST_L2, 0.9)}}
+    g.force_config(None)
+    g.cost_model_scale(-1)
+    base = picks()
+    try:
+        for term in (g.COST_SLAB, g.COST_HBM, g.COST_L2, g.COST_FIXED):
+            for factor in (0.9, 1.1):
+                g.cost_model_scale(-1)
+                g.cost_model_scale(term, factor)
+                now = picks()
+                for sh in base:
+                    if now[sh] != base[sh]:
+                        assert (term, factor) in known.get(sh, ()), (sh, term, factor, base[sh], now[sh])
+    finally:
+        g.cost_model_scale(-1)
+    assert picks() == base
