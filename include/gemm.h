@@ -22,8 +22,12 @@
  *   of columns, column-major: number of rows); otherwise ld must be at least
  *   that value.  Elements between the packed extent and ld are never written.
  *   Those of A and B may be read (nothing past an operand's last element is),
- *   but their values, NaN included, never influence C.  Pointers need only element alignment; 16-byte aligned bases with
- *   leading dimensions that are multiples of 16 bytes take the fastest kernels.
+ *   but their values, NaN included, never influence C.  Pointers need only
+ *   element alignment.  Bases and leading dimensions that are multiples of 4
+ *   bytes (always the case for binary32) take the direct-load kernels, multiples
+ *   of 16 bytes make them fastest; 16-bit operands that are only 2-byte aligned,
+ *   and M- or N-contiguous operands whose extent in that direction is not a
+ *   multiple of 16 bytes, take slower kernels that stage loads through registers.
  *
  * Element types
  *   gemm_f32    : binary32 operands, IEEE binary32 multiply-add, binary32 C.
@@ -148,7 +152,7 @@ int gemm_f16f32_noalloc(int64_t M, int64_t N, int64_t K,
 /*
  * Kernel-configuration control (the paper tunes the block tile per input size,
  * Section 5.3; here a heuristic picks it and this hook overrides it).
- * name is "auto" / NULL for the heuristic, or "<tile>[:s<slices>][:safe][:direct|:staged]" with
+ * name is "auto" / NULL for the heuristic, or "<tile>[:s<slices>][:safe][:direct|:staged][:regload]" with
  * <tile> a configuration name or "auto", e.g. "t256x256", "t128x128:s4",
  * "auto:s2:safe".  A slice count beyond the number of K slabs means one slab
  * per slice.  ":safe" runs the same kernels with every hand-over of a
@@ -159,7 +163,8 @@ int gemm_f16f32_noalloc(int64_t M, int64_t N, int64_t K,
  * registers (the path edge tiles always take), ":staged" stages whole rows of
  * every interior tile through shared memory (Section 3.2, "Epilog") wherever
  * the rows of C start on 16-byte boundaries; without either the library picks
- * by shape.  Returns GEMM_ERR_UNSUPPORTED for an unknown name.
+ * by shape.  ":regload" runs the register-staged kernels whatever the
+ * alignment.  Returns GEMM_ERR_UNSUPPORTED for an unknown name.
  * The setting is process-wide.
  */
 int gemm_force_config(const char *name);
@@ -183,9 +188,11 @@ int gemm_cost_model_scale(int term, double factor);
  * The configuration the selection would pick (or the forced one), without touching the
  * device: elem_bytes is 2 (16-bit operands) or 4 (binary32); aligned is the alignment in
  * bytes that the bases and leading dimensions of A and B share: 16 or more (or 1, "yes")
- * means they qualify for the direct-load kernels, 8, 4 (or 0, "no") the register-staged
- * kernels, 2 the register-staged kernels on operands whose 16-byte loads the memory
- * pipeline has to split.  Writes "<tile>:s<splits>" into buf (NUL-terminated, truncated to buflen).
+ * means the direct-load kernels at their best, 8 or 4 the direct-load kernels on rows that
+ * straddle cache lines, 2 the register-staged kernels on operands whose 16-byte loads the
+ * memory pipeline has to split, 0 ("no") the register-staged kernels for another reason (an
+ * operand extent that is not a multiple of the 16-byte granule).  Writes "<tile>:s<splits>"
+ * into buf (NUL-terminated, truncated to buflen).
  * This is the host side of the per-size tuning of Section 5.3, exposed so that it can be
  * tested without a GPU.
  */

@@ -113,8 +113,9 @@ struct TileConfig {
     int fallback;               // -1, or (K split across the waves of a workgroup) the tile that takes
                                 // operands this kernel does not serve: not 16-byte aligned, ragged K
     int auto16, auto32;         // load paths (bit 0: direct loads, bit 1: register-staged, bit 2: register-staged on
-                                // 2-byte aligned operands) for which the automatic selection considers this
-                                // configuration, for 16-bit and for binary32 operands; 0: only when forced
+                                // 2-byte aligned operands, bit 3: direct loads on 4-/8-byte aligned operands) for
+                                // which the automatic selection considers this configuration, for 16-bit and for
+                                // binary32 operands; 0: only when forced
 };
 
 // Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
@@ -127,14 +128,14 @@ struct TileConfig {
 // across the waves of a workgroup ties with the 2x2 arrangement of the same tile at 1024^3 and loses
 // 5-25 % elsewhere (four waves already occupy every SIMD of a CU here).  All of them can be forced.
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 2), -1, 7, 7},
-    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 128, 2, 2), -1, 7, 7},
-    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, 4, GEMM_TILE_LAUNCHERS(64, 64, 2, 2), -1, 7, 7},
-    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 4), -1, 7, 7},
+    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 2), -1, 15, 15},
+    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 128, 2, 2), -1, 15, 15},
+    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, 4, GEMM_TILE_LAUNCHERS(64, 64, 2, 2), -1, 15, 15},
+    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 4), -1, 15, 15},
     {"t256x128", 256, 128, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(256, 128, 2, 2), -1, 0, 0},
     {"t128x256", 128, 256, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(128, 256, 2, 2), -1, 0, 0},
-    {"t128x64", 128, 64, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 6, 0},
-    {"t64x128", 64, 128, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 6, 0},
+    {"t128x64", 128, 64, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 14, 0},
+    {"t64x128", 64, 128, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 14, 0},
     // K split across the four waves of the workgroup (Section 5.3, small sizes)
     {"k64x64", 64, 64, 4, 0.12, 0.65, 0.45, 1.9, 1.0, 1, launch_ksplit<_Float16, 64, 64>, launch_ksplit<float, 64, 64>,
      launch_ksplit<__bf16, 64, 64>, 2, 0, 0},
@@ -145,6 +146,7 @@ std::mutex g_mutex;
 int g_forced_tile = -1;    // -1: heuristic
 int g_forced_splits = 0;   // 0: heuristic
 bool g_forced_safe = false;
+bool g_force_regload = false;  // ":regload" in a forced configuration: register-staged kernels whatever the alignment
 int g_store_mode = 0;  // 0: by shape; 1: ":direct", C straight from registers; 2: ":staged", through LDS where possible
 double g_cost_scale[GEMM_COST_TERMS] = {1.0, 1.0, 1.0, 1.0};
 unsigned long long *g_trace = nullptr;  // profiling aid (gemm_set_phase_trace)
@@ -174,7 +176,8 @@ int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // bytes the resident workgroups keep in flight), and L2->CU traffic for all the bytes the
 // workgroups pull; plus launch/fill/drain and, with K slices, the reduce pass.
 // path: 0 = direct-load kernels, 1 = register-staged loads, 2 = register-staged loads of operands
-// that are only 2-byte aligned (each 16-byte load is then split up by the memory pipeline)
+// that are only 2-byte aligned (each 16-byte load is then split up by the memory pipeline),
+// 3 = direct-load kernels on operands that are 4- or 8-byte aligned (row pieces straddle cache lines)
 double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64_t KT, int splits, bool f32,
                      int path, int NUM_CU)
 {
@@ -188,7 +191,9 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
     const int64_t share = cdiv(W, NUM_CU) < t.wg_per_cu ? cdiv(W, NUM_CU) : t.wg_per_cu;
     const double alone = f32 ? t.f32_alone : t.f16_alone, full = f32 ? t.f32_full : t.f16_full;
     double slab = alone + (t.wg_per_cu > 1 ? (full - alone) * (double)(share - 1) / (t.wg_per_cu - 1) : 0.0);
-    if (path != 0) {
+    if (path == 3) {
+        slab *= f32 ? 1.0 : 1.15;   // measured 1.0 (binary32) .. 1.1-1.3 (16-bit, K-contiguous rows) of the aligned time
+    } else if (path != 0) {
         // the register-staged path keeps `depth` slabs in flight per workgroup: a slab cannot take
         // less than that share of a global-load round trip
         // (binary32 slabs are bound by their MFMA time: measured within 5 % of the direct path)
@@ -228,6 +233,8 @@ void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int
         for (int s = 1; s <= 32; s *= 2) {
             const int cand = forced > 0 ? forced : s;
             if (cand > 1 && cand > KT) break;
+            // the rectangular tiles were only ever ahead without K slices (mid-size products)
+            if (g_forced_tile < 0 && forced == 0 && cand > 1 && kTiles[t].BM != kTiles[t].BN) break;
             if (forced == 0 && cand > 1 && max_ws_bytes > 0 &&
                 (size_t)cand * (size_t)M * (size_t)N * sizeof(float) > max_ws_bytes)
                 break;
@@ -350,16 +357,23 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     const bool akc = layA == GEMM_ROW_MAJOR;  // A(i,k) contiguous in k
     const bool bkc = layB == GEMM_COL_MAJOR;  // B(k,j) contiguous in k
     constexpr int EPC = Elem<T>::EPC, BK = Elem<T>::BK;
-    bool aligned = ((uintptr_t)A % 16 == 0) && ((uintptr_t)B % 16 == 0) && (lda % EPC == 0) && (ldb % EPC == 0);
+    // The direct global->LDS loads need 4-byte aligned addresses only (measured: bit-exact, and faster
+    // than staging through registers); 16-byte aligned operands make every 128-byte row piece one cache
+    // line and are the fastest class.  An M/N-contiguous operand whose extent is not a multiple of the
+    // 16-byte granule has granules that straddle its edge: those, operands that are only 2-byte aligned
+    // and leading dimensions too long for 32-bit tile offsets take the register-staged kernels.
+    const uintptr_t low_bits = (uintptr_t)A | (uintptr_t)B | (uintptr_t)(lda * (int64_t)sizeof(T)) |
+                               (uintptr_t)(ldb * (int64_t)sizeof(T));
+    bool aligned = (low_bits & 3) == 0;   // "aligned" from here on: served by the direct-load kernels
     if (!akc && M % EPC != 0) aligned = false;
     if (!bkc && N % EPC != 0) aligned = false;
-
     // the direct loaders address a tile with 32-bit byte offsets from its origin
     const bool ld32 = 256 * lda * (int64_t)sizeof(T) < (1LL << 31) && 256 * ldb * (int64_t)sizeof(T) < (1LL << 31);
     if (!ld32) aligned = false;
-    const uintptr_t low_bits = (uintptr_t)A | (uintptr_t)B | (uintptr_t)(lda * (int64_t)sizeof(T)) |
-                               (uintptr_t)(ldb * (int64_t)sizeof(T));
-    const int path = aligned ? 0 : ((low_bits & 3) != 0 ? 2 : 1);
+    if (g_force_regload) aligned = false;
+    // load path for the cost model: 0 direct loads on 16-byte aligned operands, 3 direct loads on 4- or
+    // 8-byte aligned ones, 1 register-staged, 2 register-staged on 2-byte aligned operands
+    const int path = aligned ? ((low_bits & 15) == 0 ? 0 : 3) : ((low_bits & 3) != 0 ? 2 : 1);
 
     // From here to the last launch under the lock: the selection reads the process-wide
     // overrides, and a K-sliced call's two launches must reach the stream back to back (another
@@ -461,7 +475,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         if (rc != hipSuccess) return GEMM_ERR_HIP;
     }
     snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d%s%s", type_name, t.name,
-             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? "aligned" : "general", splits, a.safe ? " safe" : "",
+             akc ? 'N' : 'T', bkc ? 'T' : 'N', aligned ? (path == 0 ? "aligned" : "aligned4") : "general", splits, a.safe ? " safe" : "",
              noalloc && splits > 1 ? " static-scratch" : "");
     return GEMM_OK;
 }
@@ -515,8 +529,10 @@ int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int align
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
-        choose(M, N, K, KT, f32, aligned == 1 || aligned >= 16 ? 0 : (aligned == 2 ? 2 : 1), kDefaultNumCU, 0,
-               (aligned == 1 || aligned >= 16) && K % BK == 0, tile, splits);
+        // 16 or more (or 1): direct loads, aligned; 8 or 4: direct loads on misaligned rows; 0: register-staged
+        // (operand extents that are not multiples of the granule); 2: register-staged, 2-byte aligned
+        const int path = (aligned == 1 || aligned >= 16) ? 0 : (aligned == 2 ? 2 : (aligned >= 4 ? 3 : 1));
+        choose(M, N, K, KT, f32, path, kDefaultNumCU, 0, (path == 0 || path == 3) && K % BK == 0, tile, splits);
     }
     const int64_t per = cdiv(KT, splits);
     splits = (int)cdiv(KT, per);  // no empty slices, as in the launch path
@@ -532,17 +548,20 @@ int gemm_force_config(const char *name)
         g_forced_splits = 0;
         g_forced_safe = false;
         g_store_mode = 0;
+        g_force_regload = false;
         return GEMM_OK;
     }
-    // "<tile|auto>[:s<slices>][:safe][:direct|:staged]"
+    // "<tile|auto>[:s<slices>][:safe][:direct|:staged][:regload]"
     std::string s(name);
     int splits = 0, store_mode = 0;
-    bool safe = false;
+    bool safe = false, regload = false;
     size_t colon;
     while ((colon = s.rfind(':')) != std::string::npos) {
         const std::string tail = s.substr(colon + 1);
         if (tail == "safe") {
             safe = true;
+        } else if (tail == "regload") {
+            regload = true;
         } else if (tail == "direct" || tail == "staged") {
             if (store_mode != 0) return GEMM_ERR_UNSUPPORTED;
             store_mode = tail == "direct" ? 1 : 2;
@@ -565,6 +584,7 @@ int gemm_force_config(const char *name)
     g_forced_splits = splits;
     g_forced_safe = safe;
     g_store_mode = store_mode;
+    g_force_regload = regload;
     return GEMM_OK;
 }
 

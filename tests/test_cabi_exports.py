@@ -61,20 +61,27 @@ def test_selection_of_tile_and_k_slices():
     assert q(2, 4097, 3073, 1025, aligned=False) == "t256x256w8:s1"
     # mid-size products on the register-staged path: the 128x64 / 64x128 tiles (measured 2-9 % ahead of 64x64)
     assert q(2, 1000, 1500, 2000, aligned=False) in ("t128x64:s1", "t64x128:s1")
-    assert q(2, 1536, 1024, 2048, aligned=8) in ("t128x64:s1", "t64x128:s1")
-    # ... and never for 16-byte aligned operands or binary32, where they tie or lose
+    assert q(2, 1536, 1024, 2048, aligned=2) in ("t128x64:s1", "t64x128:s1")
+    # ... and never for 16-byte aligned operands, binary32 or K-sliced shapes, where they tie or lose
     assert q(2, 1536, 1024, 2048) == "t64x64:s1"
+    assert q(2, 1536, 1024, 2048, aligned=8) in ("t128x64:s1", "t64x128:s1")   # direct loads on misaligned rows: 15 % ahead
     assert q(4, 4096, 4096, 4096) == "t256x256:s1"
-    # register-staged kernels (bases or leading dimensions not 16-byte aligned): the alignment
-    # class is passed in bytes; mid-size shapes take the 128x128 tile, which keeps three slabs in
-    # flight in registers, and small ones are not cut into K slices
-    for align in (8, 4, 2):
+    # The alignment class is passed in bytes.  4- and 8-byte aligned operands run the direct-load
+    # kernels (their rows straddle cache lines) and get the picks of the aligned class here;
+    # 2-byte aligned ones and operands with ragged granules (aligned=False) the register-staged
+    # kernels: mid-size shapes then take the 128x128 tile, which keeps three slabs in flight in
+    # registers, big ones the 8-wave tile, and small ones are not cut into K slices
+    for align in (8, 4):
+        assert q(2, 2048, 2048, 2048, aligned=align) == "t128x128:s1"
+        assert q(2, 1024, 1024, 1024, aligned=align) == "t64x64:s1"
+        assert q(2, 4096, 4096, 4096, aligned=align) == "t256x256:s1"
+        assert q(2, 8192, 128, 8192, aligned=align) == "t128x128:s4"
+    for align in (2, False):
         assert q(2, 2048, 2048, 2048, aligned=align) == "t128x128:s1"
         assert q(2, 1024, 1024, 1024, aligned=align) == "t64x64:s1"
         assert q(2, 512, 512, 512, aligned=align) == "t64x64:s1"
         assert q(2, 4096, 4096, 1024, aligned=align) == "t256x256w8:s1"
     assert q(2, 2048, 2048, 2048, aligned=16) == q(2, 2048, 2048, 2048, aligned=True)
-    assert q(2, 2048, 2048, 2048, aligned=8) == q(2, 2048, 2048, 2048, aligned=False)
     assert q(4, 2048, 2048, 2048, aligned=4) == "t128x128:s1"
     assert q(4, 256, 256, 256) == "t64x64:s1"
     # never more slices than K slabs (64 k for binary16, 32 k for binary32), none without K to spare
@@ -138,7 +145,7 @@ def test_forced_slice_count_beyond_the_slab_count_still_costs_every_tile():
 def test_force_config_suffixes():
     import paper_2003_06324_amd as g
     try:
-        for name in ("t64x64:safe", "t64x64:s2:safe", "auto:safe", "auto:s2:direct", "t128x128:direct:safe:s3", "t64x64:staged"):
+        for name in ("t64x64:safe", "t64x64:s2:safe", "auto:safe", "auto:s2:direct", "t128x128:direct:safe:s3", "t64x64:staged", "auto:regload", "t64x64:s2:regload:safe"):
             assert g.force_config(name, check=False) == 0, name
         for name in ("t64x64:s2:s3", "t64x64:fast", ":safe", "t64x64:s0", "auto:direct:staged"):
             assert g.force_config(name, check=False) == -3, name

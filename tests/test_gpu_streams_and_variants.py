@@ -186,3 +186,42 @@ def test_k_split_across_the_waves_of_a_workgroup(oracle, dtype, out):
                 C, cfg = run_gpu(dtype, A, B, la, lb, force=tile, return_config=True)
                 assert tile in cfg.split()
                 check(C, ref, A, B, dtype, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32", "bf16"])
+def test_direct_loads_on_four_byte_aligned_operands(oracle, dtype):
+    # Bases and leading dimensions that are multiples of 4 bytes but not of 16 run the direct
+    # global->LDS loads (the configuration string says "aligned4"): every tile, all layouts, base
+    # offsets and row paddings of 4, 8 and 12 bytes, K slices, a ragged K tail.  The same inputs
+    # through the register-staged kernels (":regload") must give the same bits.
+    import paper_2003_06324_amd as g
+    esz = 4 if dtype == "f32" else 2
+    for (M, N, K) in [(264, 136, 200), (512, 384, 324)]:
+        A, B = gi.make_problem(71 + M, M, N, K, "int", dtype)
+        if dtype == "bf16":
+            ref = oracle.gemm(M, N, K, gi.bfloat16_bits(A), 0, gi.bfloat16_bits(B), 0, "bf16").astype(np.float32)
+        else:
+            ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for tile in g.config_names():
+            for la, lb in LAYOUT_PAIRS:
+                for off_bytes, pad_bytes in ((4, 0), (8, 8), (12, 4), (0, 12)):
+                    offs = (off_bytes // esz, off_bytes // esz, 0)
+                    pads = (pad_bytes // esz, pad_bytes // esz, 0)
+                    for how in ("", ":s2", ":regload"):
+                        C, cfg = run_gpu(dtype, A, B, la, lb, pads=pads, offsets=offs, force=tile + how, return_config=True)
+                        assert ("general" if how == ":regload" else "aligned4") in cfg.split(), cfg
+                        assert np.array_equal(C, ref), (dtype, M, N, K, la, lb, offs, pads, cfg)
+
+
+def test_register_staged_kernels_forced_on_aligned_operands(oracle):
+    # ":regload" keeps the register-staged pipeline reachable for operands the direct loads serve
+    import paper_2003_06324_amd as g
+    for dtype in ("f16", "f32"):
+        bk = 32 if dtype == "f32" else 64
+        A, B = gi.make_problem(73, 300, 264, 7 * bk + 8, "int", dtype)
+        ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for tile in g.config_names():
+            for la, lb in LAYOUT_PAIRS:
+                C, cfg = run_gpu(dtype, A, B, la, lb, force=tile + ":regload", return_config=True)
+                assert "general" in cfg.split(), cfg
+                assert np.array_equal(C, ref), (dtype, tile, la, lb, cfg)
