@@ -25,9 +25,8 @@
  *   but their values, NaN included, never influence C.  Pointers need only
  *   element alignment.  Bases and leading dimensions that are multiples of 4
  *   bytes (always the case for binary32) take the direct-load kernels, multiples
- *   of 16 bytes make them fastest; 16-bit operands that are only 2-byte aligned,
- *   and M- or N-contiguous operands whose extent in that direction is not a
- *   multiple of 16 bytes, take slower kernels that stage loads through registers.
+ *   of 16 bytes make them fastest; 16-bit operands that are only 2-byte aligned
+ *   take slower kernels that stage loads through registers.
  *
  * Element types
  *   gemm_f32    : binary32 operands, IEEE binary32 multiply-add, binary32 C.
@@ -190,8 +189,8 @@ int gemm_cost_model_scale(int term, double factor);
  * bytes that the bases and leading dimensions of A and B share: 16 or more (or 1, "yes")
  * means the direct-load kernels at their best, 8 or 4 the direct-load kernels on rows that
  * straddle cache lines, 2 the register-staged kernels on operands whose 16-byte loads the
- * memory pipeline has to split, 0 ("no") the register-staged kernels for another reason (an
- * operand extent that is not a multiple of the 16-byte granule).  Writes "<tile>:s<splits>"
+ * memory pipeline has to split, 0 ("no") the register-staged kernels for another reason (a
+ * leading dimension too long for 32-bit tile offsets, a forced ":regload").  Writes "<tile>:s<splits>"
  * into buf (NUL-terminated, truncated to buflen).
  * This is the host side of the per-size tuning of Section 5.3, exposed so that it can be
  * tested without a GPU.

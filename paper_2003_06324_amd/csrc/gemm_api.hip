@@ -135,7 +135,7 @@ const TileConfig kTiles[] = {
     {"t256x128", 256, 128, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(256, 128, 2, 2), -1, 0, 0},
     {"t128x256", 128, 256, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(128, 256, 2, 2), -1, 0, 0},
     {"t128x64", 128, 64, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 14, 0},
-    {"t64x128", 64, 128, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 14, 0},
+    {"t64x128", 64, 128, 2, 0.24, 0.78, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 14, 0},
     // K split across the four waves of the workgroup (Section 5.3, small sizes)
     {"k64x64", 64, 64, 4, 0.12, 0.65, 0.45, 1.9, 1.0, 1, launch_ksplit<_Float16, 64, 64>, launch_ksplit<float, 64, 64>,
      launch_ksplit<__bf16, 64, 64>, 2, 0, 0},
@@ -359,14 +359,13 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     constexpr int EPC = Elem<T>::EPC, BK = Elem<T>::BK;
     // The direct global->LDS loads need 4-byte aligned addresses only (measured: bit-exact, and faster
     // than staging through registers); 16-byte aligned operands make every 128-byte row piece one cache
-    // line and are the fastest class.  An M/N-contiguous operand whose extent is not a multiple of the
-    // 16-byte granule has granules that straddle its edge: those, operands that are only 2-byte aligned
-    // and leading dimensions too long for 32-bit tile offsets take the register-staged kernels.
+    // line and are the fastest class.  Operands that are only 2-byte aligned and leading dimensions too
+    // long for 32-bit tile offsets take the register-staged kernels.
     const uintptr_t low_bits = (uintptr_t)A | (uintptr_t)B | (uintptr_t)(lda * (int64_t)sizeof(T)) |
                                (uintptr_t)(ldb * (int64_t)sizeof(T));
     bool aligned = (low_bits & 3) == 0;   // "aligned" from here on: served by the direct-load kernels
-    if (!akc && M % EPC != 0) aligned = false;
-    if (!bkc && N % EPC != 0) aligned = false;
+    // granules of an M/N-contiguous operand straddle its edge when the extent is not a multiple of the granule
+    const bool ragged = (!akc && M % EPC != 0) || (!bkc && N % EPC != 0);
     // the direct loaders address a tile with 32-bit byte offsets from its origin
     const bool ld32 = 256 * lda * (int64_t)sizeof(T) < (1LL << 31) && 256 * ldb * (int64_t)sizeof(T) < (1LL << 31);
     if (!ld32) aligned = false;
@@ -386,7 +385,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
-    const bool ksplit_ok = aligned && K % BK == 0;
+    const bool ksplit_ok = aligned && !ragged && K % BK == 0;
     choose(M, N, K, KT, f32, path, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, ksplit_ok, tile, splits);
     if (kTiles[tile].fallback >= 0 && !ksplit_ok) tile = kTiles[tile].fallback;  // forced, but not served by that kernel
     const TileConfig &t = kTiles[tile];

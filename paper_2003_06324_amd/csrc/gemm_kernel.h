@@ -596,7 +596,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         // two tiles of MFMA time to land and Y slabs one.  Past the end of K the loaders
         // re-fetch the last slab (never read), which keeps the loop body branch-free and
         // the number of outstanding loads constant for the counted waits.
-        const int n = (kend - k_done) / BK;
+        // A granule of an M/N-contiguous operand that straddles the matrix edge is read whole (its
+        // tail, padding or the start of the next k-row, only feeds tile rows that are never
+        // stored); on the operand's last k-row that tail could lie past the operand, so a tile
+        // with such granules leaves the slab holding that row to the guarded loop below.
+        constexpr int EPC_ = Elem<T>::EPC;
+        const bool edge_a = !AKC && p.M % EPC_ != 0 && m0 + BM > p.M;
+        const bool edge_b = !BKC && p.N % EPC_ != 0 && n0 + BN > p.N;
+        const bool narrow = (edge_a && p.lda < 2 * EPC_) || (edge_b && p.ldb < 2 * EPC_);
+        int n = (kend - k_done) / BK;
+        if ((edge_a || edge_b) && k_done + n * BK == p.K) --n;
+        if (narrow) n = 0;
         if (n > 0) {
             DirectLoader<T, BM, NW, AKC> la;
             DirectLoader<T, BN, NW, BKC> lb;
