@@ -31,11 +31,17 @@ def draw_case(rng):
         K = int(rng.integers(1, 1500))
     la, lb, lc = (int(rng.integers(0, 2)) for _ in range(3))
     epc = 8 if dtype == "f16" else 4
-    pads = tuple(int(rng.choice([0, 0, epc, 2 * epc, 1, 3, 5])) for _ in range(3))
-    offs = tuple(int(rng.choice([0, 0, 0, epc, 1, 2])) for _ in range(3))
+    # paddings and base offsets in elements: multiples of the 16-byte granule, of 4 bytes (direct loads on rows
+    # that straddle cache lines) and odd counts (2-byte aligned binary16: register-staged loads)
+    pads = tuple(int(rng.choice([0, 0, epc, 2 * epc, 1, 3, 5, 2, 4, 6])) for _ in range(3))
+    offs = tuple(int(rng.choice([0, 0, 0, epc, 1, 2, 4, 6])) for _ in range(3))
     force = None
     if rng.random() < 0.7:
         force = "%s:s%d" % (rng.choice(TILES), int(rng.choice([1, 1, 1, 2, 3, 4, 7])))
+        # variants of the same kernels: fully synchronised hand-overs, either store path, register-staged loads
+        for suffix, prob in ((":safe", 0.15), (str(rng.choice([":direct", ":staged"])), 0.3), (":regload", 0.15)):
+            if rng.random() < prob:
+                force += suffix
     out = "f16" if (dtype == "f16" and rng.random() < 0.3) else "f32"
     return dtype, M, N, K, la, lb, lc, pads, offs, force, out
 
