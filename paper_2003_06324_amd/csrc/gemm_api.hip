@@ -111,7 +111,7 @@ struct TileConfig {
     int depth;                  // slabs that path keeps in flight in registers
     launch_fn f16, f32, bf16;
     int fallback;               // -1, or (K split across the waves of a workgroup) the tile that takes
-                                // operands this kernel does not serve: not 16-byte aligned, ragged K
+                                // operands this kernel does not serve: 2-byte aligned, ragged granules, ragged K
     int auto16, auto32;         // load paths (bit 0: direct loads, bit 1: register-staged, bit 2: register-staged on
                                 // 2-byte aligned operands, bit 3: direct loads on 4-/8-byte aligned operands) for
                                 // which the automatic selection considers this configuration, for 16-bit and for

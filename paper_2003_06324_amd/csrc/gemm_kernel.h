@@ -24,10 +24,12 @@
 //
 // Both images are produced by direct 16-byte global->LDS loads (each wave fills
 // 1 KiB of LDS per instruction, lane l writing bytes [16l, 16l+16), so the
-// swizzle is applied by choosing which global granule a lane fetches); for
-// operands that are not 16-byte aligned by the same granules fetched through
-// registers and written to the same positions; and for ragged K tails by
-// guarded loads through registers.
+// swizzle is applied by choosing which global granule a lane fetches; the
+// global address of a granule needs 4-byte alignment only); for operands that
+// are only 2-byte aligned by the same granules fetched through registers and
+// written to the same positions; and for ragged K tails by guarded loads
+// through registers.  The tile of C leaves through LDS as well when its rows
+// allow 16-byte stores (see the epilogue).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -229,7 +231,7 @@ struct DirectLoader {
                      : "memory", "m0", "scc");
     }
 
-    // The same granule through a register instead (operands whose rows are not 16-byte
+    // The same granule through a register instead (operands whose rows are only 2-byte
     // aligned cannot use the direct loads): a 16-byte load that needs element alignment only,
     // and the store that puts it where the direct load would have put it.
     __device__ __forceinline__ uint4_t fetch1(int i) const
@@ -740,7 +742,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(const KernelArgs
         }
     }
     if (!ALIGNED) {
-        // Operands that are not 16-byte aligned: full slabs go through registers into two LDS
+        // Operands the direct loads do not serve (2-byte aligned, or forced): full slabs go through registers into two LDS
         // buffers (the same image as the direct loads make).  Per slab s: k-groups 0,1 multiply;
         // k-group 2 also writes slab s+1 (in registers since an earlier slab) to the other
         // buffer; wait for the own LDS traffic, one barrier; k-group 3 also issues the global

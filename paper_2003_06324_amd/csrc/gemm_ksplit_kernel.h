@@ -11,7 +11,7 @@
 //            issue X(t+2) into the spare slot; multiply slab t-1 meanwhile;
 //            wait: own fetches done, all but the X(t+2) loads landed; barrier t+1;
 //            issue Y(t+2) into X(t)'s slot, which every wave has finished reading.
-// The kernel serves 16-byte aligned operands and K a multiple of the slab; the host runs the
+// The kernel serves operands the direct loads serve (4-byte aligned, whole granules) and K a multiple of the slab; the host runs the
 // two-dimensional tile of the same size otherwise.  M and N may be ragged (rows past the edge
 // re-read a valid row, their results are dropped at the store).
 #pragma once

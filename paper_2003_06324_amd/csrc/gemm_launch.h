@@ -45,7 +45,7 @@ hipError_t launch_tile(bool akc, bool bkc, bool aligned, dim3 grid, hipStream_t 
     return launch_aligned<T, BM, BN, WM, WN, false, false>(aligned, grid, s, a);
 }
 
-// K split across the waves of the workgroup; the caller passes 16-byte aligned operands and a K
+// K split across the waves of the workgroup; the caller passes operands the direct loads serve and a K
 // that is a multiple of the slab (`aligned` is part of the common signature and always true here)
 template <typename T, int BM, int BN>
 hipError_t launch_ksplit(bool akc, bool bkc, bool aligned, dim3 grid, hipStream_t s, const KernelArgs &a)
