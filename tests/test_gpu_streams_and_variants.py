@@ -225,3 +225,28 @@ def test_register_staged_kernels_forced_on_aligned_operands(oracle):
                 C, cfg = run_gpu(dtype, A, B, la, lb, force=tile + ":regload", return_config=True)
                 assert "general" in cfg.split(), cfg
                 assert np.array_equal(C, ref), (dtype, tile, la, lb, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_two_byte_aligned_operands(oracle, dtype):
+    # 16-bit operands whose bases or leading dimensions are odd element counts are only 2-byte
+    # aligned and run the register-staged kernels (16-byte loads at element alignment).  Odd leading
+    # dimensions move the misalignment from row to row, odd base offsets shift every row; edge tiles
+    # re-read rows; every tile, layout pair, K slices and a K tail.
+    import paper_2003_06324_amd as g
+    for (M, N, K) in [(264, 136, 200), (77, 300, 3 * 64 + 5), (513, 129, 2 * 64), (1, 9, 64), (130, 2, 4 * 64)]:
+        A, B = gi.make_problem(81 + M, M, N, K, "int", dtype)
+        if dtype == "bf16":
+            ref = oracle.gemm(M, N, K, gi.bfloat16_bits(A), 0, gi.bfloat16_bits(B), 0, "bf16").astype(np.float32)
+        else:
+            ref = ref_of(oracle, A, B, dtype).astype(np.float32)
+        for tile in g.config_names():
+            for la, lb in LAYOUT_PAIRS:
+                for pads, offs in (((1, 1, 0), (0, 0, 0)), ((0, 0, 0), (1, 3, 0)), ((3, 5, 0), (1, 1, 0)), ((1, 0, 0), (0, 1, 0))):
+                    for how in ("", ":s2"):
+                        C, cfg = run_gpu(dtype, A, B, la, lb, pads=pads, offsets=offs, force=tile + how, return_config=True)
+                        lda = (K if la == gi.ROW_MAJOR else M) + pads[0]
+                        ldb = (N if lb == gi.ROW_MAJOR else K) + pads[1]
+                        two_byte = any(x % 2 for x in (lda, ldb, offs[0], offs[1]))   # odd element counts
+                        assert ("general" in cfg.split()) == two_byte, (cfg, lda, ldb, offs)
+                        assert np.array_equal(C, ref), (dtype, M, N, K, la, lb, pads, offs, cfg)
