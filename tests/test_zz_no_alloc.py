@@ -62,3 +62,37 @@ def test_noalloc_refuses_what_does_not_fit_and_never_picks_it():
     g.gemm_f16f32_noalloc(M, N, K, dA, 0, 0, dB, 0, 0, dC, 0, 0, stream)
     torch.cuda.synchronize()
     assert bool((dC == 0).all())
+
+
+def test_noalloc_k_sliced_call_under_graph_capture(oracle):
+    # The use the entry point is for: a K-sliced product recorded into a HIP graph (the allocating
+    # entry point may call hipMalloc there).  The graph is replayed several times with eager work
+    # and synchronisation in between, inputs changed in place, every replay checked against the
+    # oracle bit for bit (integer-valued operands).
+    import torch
+    import paper_2003_06324_amd as g
+    M, N, K = 192, 160, 1536
+    A0, B0 = gi.make_problem(1300, M, N, K, "int", "f16")
+    dA = torch.from_numpy(gi.store(A0, gi.ROW_MAJOR).view(np.int16)).cuda()
+    dB = torch.from_numpy(gi.store(B0, gi.COL_MAJOR).view(np.int16)).cuda()
+    dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+    g.force_config("t64x64:s6")
+    try:
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            s = torch.cuda.current_stream().cuda_stream
+            g.gemm_f16f32_noalloc(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, s)
+            assert "s6 static-scratch" in g.last_config()
+    finally:
+        g.force_config(None)
+    for rep in range(4):
+        A, B = gi.make_problem(1301 + rep, M, N, K, "int", "f16")
+        dA.copy_(torch.from_numpy(gi.store(A, gi.ROW_MAJOR).view(np.int16)))
+        dB.copy_(torch.from_numpy(gi.store(B, gi.COL_MAJOR).view(np.int16)))
+        dC.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.gemm(M, N, K, A, gi.ROW_MAJOR, B, gi.ROW_MAJOR, "f16").astype(np.float32)
+        assert np.array_equal(dC.cpu().numpy().reshape(M, N), want), rep
