@@ -224,7 +224,11 @@ const char *gemm_last_config(void);
 /* Text for a status code (static storage). */
 const char *gemm_status_string(int status);
 
-/* Frees every K-slice workspace (waits for the work that still uses them).  Safe to call more than once. */
+/*
+ * Frees every K-slice workspace (waits for the work that still uses them).  Safe to call
+ * more than once.  A HIP graph that recorded a K-sliced call holds its workspace's address:
+ * such a graph must not be replayed after this call.
+ */
 int gemm_shutdown(void);
 
 #ifdef __cplusplus
