@@ -89,7 +89,8 @@ def config_rows(per_layout, S, skip_big):
             C = torch.empty(M * N, dtype=torch.float32, device="cuda")
             la, lb = gi.LAYOUTS[lay]
             fn = g.gemm_f32 if dt == "f32" else g.gemm_f16f32
-            call = (M, N, K, dA, la, 0, dB, lb, 0, C, gi.ROW_MAJOR, 0)
+            # raw addresses: for the few-microsecond shapes the binding's per-call work would otherwise show
+            call = (M, N, K, dA.data_ptr(), la, 0, dB.data_ptr(), lb, 0, C.data_ptr(), gi.ROW_MAJOR, 0)
             # back-to-back launches between two events, as the tuning sweep times them (an event after
             # every launch would add a few microseconds of its own to the small shapes); seven batches
             iters = 20 if flop > 5e10 else 100
