@@ -219,7 +219,7 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
 // max_ws_bytes: largest K-slice workspace the caller can provide (0 = no limit); automatic
 // picks that would need more are not considered.
 // ksplit_ok: the operands qualify for the kernels that split K across the waves of a workgroup
-void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
+void choose_uncached(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
             bool ksplit_ok, int &tile, int &splits)
 {
     double best = 1e300;
@@ -244,6 +244,35 @@ void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int
             if (forced > 0) break;
         }
     }
+}
+
+// The selection costs about fifty evaluations of the model; calls repeat shapes, so the last picks
+// are kept (g_mutex held; any change of the forced configuration or of the model's scales
+// starts a new epoch and thereby empties the table).
+struct Pick {
+    int64_t M = -1, N = 0, K = 0;
+    size_t max_ws = 0;
+    uint64_t epoch = 0;
+    int f32 = 0, path = 0, num_cu = 0, ksplit_ok = 0, tile = 0, splits = 0;
+};
+Pick g_picks[64];
+uint64_t g_epoch = 1;
+
+void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
+            bool ksplit_ok, int &tile, int &splits)
+{
+    const uint64_t h = (uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^
+                       (uint64_t)K * 0x165667B19E3779F9ull ^ (uint64_t)(path * 4 + f32 * 2 + ksplit_ok);
+    Pick &e = g_picks[(h >> 32) & 63];
+    if (e.M == M && e.N == N && e.K == K && e.max_ws == max_ws_bytes && e.epoch == g_epoch && e.f32 == (int)f32 &&
+        e.path == path && e.num_cu == num_cu && e.ksplit_ok == (int)ksplit_ok) {
+        tile = e.tile;
+        splits = e.splits;
+        return;
+    }
+    choose_uncached(M, N, K, KT, f32, path, num_cu, max_ws_bytes, ksplit_ok, tile, splits);
+    e.M = M; e.N = N; e.K = K; e.max_ws = max_ws_bytes; e.epoch = g_epoch; e.f32 = f32; e.path = path;
+    e.num_cu = num_cu; e.ksplit_ok = ksplit_ok; e.tile = tile; e.splits = splits;
 }
 
 bool bad_matrix(const void *p, int layout, int64_t &ld, int64_t rows, int64_t cols)
@@ -543,6 +572,7 @@ int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int align
 int gemm_force_config(const char *name)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
+    ++g_epoch;
     if (name == nullptr || strcmp(name, "auto") == 0 || name[0] == 0) {
         g_forced_tile = -1;
         g_forced_splits = 0;
@@ -600,6 +630,7 @@ int gemm_set_phase_trace(void *device_buffer, int64_t workgroups)
 int gemm_cost_model_scale(int term, double factor)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
+    ++g_epoch;
     if (term < 0) {
         for (double &x : g_cost_scale) x = 1.0;
         return GEMM_OK;
