@@ -134,7 +134,8 @@ int gemm_bf16f32(int64_t M, int64_t N, int64_t K,
  * calls hipMalloc or hipFree: the partial sums of a shape that is split along K
  * go to a fixed array of GEMM_NOALLOC_SCRATCH_BYTES that every GPU the library
  * runs on holds until the process ends.  The automatic selection only picks
- * K-slice counts whose partials (slices * M * N * 4 bytes) fit the array; a
+ * K-slice counts whose partials (slices * M * N' * 4 bytes, N' = N rounded up
+ * to a multiple of 32) fit the array; a
  * forced configuration that needs more is refused with GEMM_ERR_WORKSPACE and
  * nothing is enqueued.  All calls on one GPU share that GPU's array (its
  * contents are whatever the last call left; every call overwrites what it
@@ -196,6 +197,15 @@ int gemm_cost_model_scale(int term, double factor);
  * tested without a GPU.
  */
 int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen);
+
+/*
+ * gemm_query_config for given layouts of A (M x K) and B (K x N), GEMM_ROW_MAJOR or
+ * GEMM_COL_MAJOR each (gemm_query_config assumes both row-major): operands that are not 16-byte
+ * aligned cost more or less depending on which of them have K as their contiguous dimension, so
+ * the pick can differ.  GEMM_ERR_INVALID_ARG for any other layout value.
+ */
+int gemm_query_config_layouts(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, int layoutA, int layoutB,
+                              char *buf, int buflen);
 
 /*
  * Profiling aid (the paper times whole kernels, Section 5; this shows where inside a

@@ -49,19 +49,25 @@ namespace {
 
 // Sums the K-slices of the workspace in slice order (deterministic) into C; TC is float, or
 // _Float16 for the binary16-output entry point (one rounding, to nearest even, of the sum).
-// VEC = 4: N is a multiple of 4, so a thread handles four neighbouring columns with 16-byte
-// loads.  The loads of four slices are issued together and then added one after the other, in
-// slice order: the pass is bound by memory latency, not by the additions.
-template <typename TC, int VEC>
+// A workspace row holds ldw floats, a multiple of 32 (ws_pitch): whatever N is, a thread takes
+// four neighbouring columns with 16-byte loads, and rows begin on cache-line boundaries.  The
+// loads of four slices are issued together and then added one after the other, in slice order:
+// the pass is bound by memory latency, not by the additions.  vec_c: base and rows of C allow
+// one store of the four results.
+template <typename TC>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int64_t split_stride,
-                                                            int splits, TC *C, int64_t ldc,
-                                                            int M, int N)
+                                                            int splits, int ldw, TC *C, int64_t ldc,
+                                                            int M, int N, int vec_c)
 {
-    typedef float vec_t __attribute__((ext_vector_type(VEC)));
-    const int64_t total = (int64_t)M * N / VEC;
+    typedef float vec_t __attribute__((ext_vector_type(4)));
+    typedef TC out_t __attribute__((ext_vector_type(4)));
+    const int pieces = (N + 3) / 4;  // 16-byte pieces of a row that hold results
+    const int64_t total = (int64_t)M * pieces;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * 256) {
-        const float *src = ws + idx * VEC;
+        const int64_t r = idx / pieces;
+        const int c = (int)(idx - r * pieces) * 4;
+        const float *src = ws + r * ldw + c;
         vec_t s = 0.0f;
         int z = 0;
         for (; z + 4 <= splits; z += 4) {
@@ -75,11 +81,19 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int
             s += v3;
         }
         for (; z < splits; ++z) s += *(const vec_t *)(src + z * split_stride);
-        const int64_t e = idx * VEC;
-        const int64_t r = e / N, c = e - r * N;
         TC *dst = C + r * ldc + c;
+        if (vec_c && c + 4 <= N) {
+            out_t o;
 #pragma unroll
-        for (int x = 0; x < VEC; ++x) dst[x] = (TC)s[x];
+            for (int x = 0; x < 4; ++x) o[x] = (TC)s[x];
+            *(out_t *)dst = o;
+        } else {
+            // (the columns of the last piece beyond N were never written by the product kernel
+            // and are not stored)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (c + x < N) dst[x] = (TC)s[x];
+        }
     }
 }
 
@@ -107,8 +121,13 @@ struct TileConfig {
     int wg_per_cu;              // resident workgroups per CU (LDS-limited)
     double f16_alone, f16_full; // microseconds per 64-k slab: one workgroup on a CU / CU fully occupied
     double f32_alone, f32_full; // same per 32-k f32 slab
-    double general;             // slowdown of the register-staged (unaligned) path, 16-bit operands
-    int depth;                  // slabs that path keeps in flight in registers
+    double fixed;               // microseconds a round of tiles spends outside its K loop (first operands, stores)
+    double hbm_eff;             // share of the model's HBM rate this tile's access pattern reaches
+    double f16_a4, f32_a4;      // slab time on 4-/8-byte aligned operands (direct loads whose row pieces straddle
+                                // cache lines) over the aligned slab time
+    double f16_a2;              // same for 2-byte aligned 16-bit operands (register-staged, every 16-byte load split up)
+    double general;             // same for the register-staged path on aligned 16-bit operands
+    int depth;                  // slabs the register-staged path keeps in flight in registers
     launch_fn f16, f32, bf16;
     int fallback;               // -1, or (K split across the waves of a workgroup) the tile that takes
                                 // operands this kernel does not serve: 2-byte aligned, ragged granules, ragged K
@@ -118,28 +137,37 @@ struct TileConfig {
                                 // binary32 operands; 0: only when forced
 };
 
-// Slab times measured on MI355X with random operands (the part power-throttles to ~1.5 GHz
-// under sustained MFMA load; these are not clock-peak figures).
 #define GEMM_TILE_LAUNCHERS(BM, BN, WM, WN) \
     launch_tile<_Float16, BM, BN, WM, WN>, launch_tile<float, BM, BN, WM, WN>, launch_tile<__bf16, BM, BN, WM, WN>
-// Which configurations the automatic selection considers is a measured choice (sweep over the benchmark
-// shapes and the paper's size ranges): the rectangular tiles win only as 128x64 / 64x128 on mid-size
-// products whose operands are not 16-byte aligned (up to 9 %) and tie or lose elsewhere; splitting K
-// across the waves of a workgroup ties with the 2x2 arrangement of the same tile at 1024^3 and loses
-// 5-25 % elsewhere (four waves already occupy every SIMD of a CU here).  All of them can be forced.
+// The constants of this table and of estimate_cost are fitted, not derived: every configuration
+// at 1..32 K slices was timed on MI355X with random operands (so at the ~1.5 GHz the part
+// throttles to under sustained MFMA load) on the benchmark shapes and on 425 random shapes
+// of all layouts and alignment classes (M, N in 128..9000, K in 64..50000), the model's terms were
+// fitted to the times by least squares, and then adjusted to minimise the time lost by the
+// model's pick against the best measured configuration (fit_cost_model.py; tune_sweep.py prints that ratio).  The
+// slab times therefore absorb what the model has no term for (a lone workgroup's slab is bound
+// by load latency, not by its MFMA work) and are not clock-peak figures.
+// (64x128 before 128x64: the model often ties the two, and the tie goes to the first; 64x128 measures 4-8 % ahead)
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.6, 1.6, 7.0, 7.0, 1.25, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 2), -1, 15, 15},
-    {"t128x128", 128, 128, 2, 0.43, 1.05, 2.0, 4.0, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 128, 2, 2), -1, 15, 15},
-    {"t64x64", 64, 64, 4, 0.13, 0.70, 0.5, 2.0, 1.35, 4, GEMM_TILE_LAUNCHERS(64, 64, 2, 2), -1, 15, 15},
-    {"t256x256w8", 256, 256, 1, 1.72, 1.72, 7.1, 7.1, 1.15, 1, GEMM_TILE_LAUNCHERS(256, 256, 2, 4), -1, 15, 15},
-    {"t256x128", 256, 128, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(256, 128, 2, 2), -1, 0, 0},
-    {"t128x256", 128, 256, 1, 0.85, 0.85, 3.6, 3.6, 1.3, 1, GEMM_TILE_LAUNCHERS(128, 256, 2, 2), -1, 0, 0},
-    // (64x128 before 128x64: the model often ties the two, and the tie goes to the first; 64x128 measures 4-8 % ahead)
-    {"t64x128", 64, 128, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 14, 0},
-    {"t128x64", 128, 64, 2, 0.25, 0.80, 1.1, 2.8, 1.3, 3, GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 14, 0},
-    // K split across the four waves of the workgroup (Section 5.3, small sizes)
-    {"k64x64", 64, 64, 4, 0.12, 0.65, 0.45, 1.9, 1.0, 1, launch_ksplit<_Float16, 64, 64>, launch_ksplit<float, 64, 64>,
-     launch_ksplit<__bf16, 64, 64>, 2, 0, 0},
+    {"t256x256", 256, 256, 1, 1.1, 1.1, 7.56, 7.56, 5.15, 0.747, 1.01, 0.969, 2.11, 1.25, 1,
+     GEMM_TILE_LAUNCHERS(256, 256, 2, 2), -1, 15, 15},
+    {"t128x128", 128, 128, 2, 0.505, 0.847, 1.88, 3.26, 1.46, 1.31, 1.16, 0.979, 1.62, 1.3, 3,
+     GEMM_TILE_LAUNCHERS(128, 128, 2, 2), -1, 15, 15},
+    {"t64x64", 64, 64, 4, 0.281, 0.72, 0.484, 1.71, 1.21, 0.862, 1.1, 0.995, 1.48, 1.35, 4,
+     GEMM_TILE_LAUNCHERS(64, 64, 2, 2), -1, 15, 15},
+    {"t256x256w8", 256, 256, 1, 1.15, 1.15, 6.99, 6.99, 3.35, 0.681, 1.02, 1.01, 1.21, 1.15, 1,
+     GEMM_TILE_LAUNCHERS(256, 256, 2, 4), -1, 15, 15},
+    {"t256x128", 256, 128, 1, 0.83, 0.83, 3.58, 3.58, 2.97, 1.2, 1.1, 0.963, 1.54, 1.3, 1,
+     GEMM_TILE_LAUNCHERS(256, 128, 2, 2), -1, 15, 15},
+    {"t128x256", 128, 256, 1, 0.725, 0.725, 3.36, 3.36, 3.12, 1.29, 1.09, 1.11, 1.88, 1.3, 1,
+     GEMM_TILE_LAUNCHERS(128, 256, 2, 2), -1, 15, 15},
+    {"t64x128", 64, 128, 2, 0.362, 0.593, 0.889, 1.7, 1.42, 0.954, 1.26, 0.996, 1.62, 1.3, 3,
+     GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 15, 15},
+    {"t128x64", 128, 64, 2, 0.367, 0.595, 0.965, 1.65, 1.34, 0.919, 1.32, 1.03, 1.73, 1.3, 3,
+     GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 15, 15},
+    // K split across the four waves of the workgroup (Section 5.3, small sizes); fitted on 16-byte aligned operands only
+    {"k64x64", 64, 64, 4, 0.29, 0.712, 0.545, 1.83, 2.32, 0.856, 1.1, 0.995, 1.48, 1.0, 1,
+     launch_ksplit<_Float16, 64, 64>, launch_ksplit<float, 64, 64>, launch_ksplit<__bf16, 64, 64>, 2, 1, 1},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -171,6 +199,11 @@ thread_local char t_last_config[128] = "none";
 
 int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Floats per row of a K-slice workspace: rows begin on 128-byte boundaries whatever N is, so the
+// partial results go out, and are read back by the reduce pass, in 16-byte pieces.
+int64_t ws_pitch(int64_t N) { return cdiv(N, 32) * 32; }
+size_t ws_bytes(int64_t splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)ws_pitch(N) * sizeof(float); }
+
 // Estimated run time in microseconds of (tile, splits) on this shape.  Three floors: the
 // MFMA work as scheduled on 256 CUs (rounds of resident workgroups, slab time depending on
 // how many workgroups share a CU), HBM traffic for the unique bytes (limited by how many
@@ -179,9 +212,13 @@ int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // path: 0 = direct-load kernels, 1 = register-staged loads, 2 = register-staged loads of operands
 // that are only 2-byte aligned (each 16-byte load is then split up by the memory pipeline),
 // 3 = direct-load kernels on operands that are 4- or 8-byte aligned (row pieces straddle cache lines)
+// k_contig: how many of A and B have K as their contiguous dimension (0..2); the misaligned
+// classes depend on it (a K-contiguous row is what straddles lines or gets its loads split)
 double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64_t KT, int splits, bool f32,
-                     int path, int NUM_CU)
+                     int path, int k_contig, int NUM_CU)
 {
+    static const double kLayA4[3] = {0.881, 1.0, 0.86};  // 16-bit, path 3, by k_contig
+    static const double kLayA2[3] = {0.884, 1.0, 1.2};   // 16-bit, path 2
     const double *const scale = g_cost_scale;
     const int64_t tiles = cdiv(M, t.BM) * cdiv(N, t.BN);
     const int64_t per = cdiv(KT, splits);
@@ -192,35 +229,42 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
     const int64_t share = cdiv(W, NUM_CU) < t.wg_per_cu ? cdiv(W, NUM_CU) : t.wg_per_cu;
     const double alone = f32 ? t.f32_alone : t.f16_alone, full = f32 ? t.f32_full : t.f16_full;
     double slab = alone + (t.wg_per_cu > 1 ? (full - alone) * (double)(share - 1) / (t.wg_per_cu - 1) : 0.0);
+    // slabs' worth of extra time for the guarded last slab of a ragged K
+    double tail = f32 ? (path == 3 ? 1.88 : 1.44) : (path == 3 ? 2.55 : 2.54);
     if (path == 3) {
-        slab *= f32 ? 1.0 : 1.15;   // measured 1.0 (binary32) .. 1.1-1.3 (16-bit, K-contiguous rows) of the aligned time
+        slab *= f32 ? t.f32_a4 : t.f16_a4 * kLayA4[k_contig];
     } else if (path != 0) {
         // the register-staged path keeps `depth` slabs in flight per workgroup: a slab cannot take
         // less than that share of a global-load round trip
         // (binary32 slabs are bound by their MFMA time: measured within 5 % of the direct path)
-        slab *= f32 ? 1.05 : t.general * (path == 2 ? 1.5 : 1.0);
+        slab *= f32 ? 1.05 : (path == 2 ? t.f16_a2 * kLayA2[k_contig] : t.general);
         const double floor = 1.2 / ((double)share * t.depth);
         if (slab < floor) slab = floor;
+        if (!f32) tail = 3.77;
     }
     slab *= scale[GEMM_COST_SLAB];
-    const double t_mfma = rounds * ((double)per * slab + 1.0);
+    double t_mfma = rounds * ((double)per * slab + t.fixed);
+    if (K % (f32 ? 32 : 64) != 0) t_mfma += tail * slab;
     const double esz = f32 ? 4.0 : 2.0;
     const double unique = ((double)M * K + (double)K * N) * esz + (double)M * N * 4.0;
     const double resident = (double)W < slots ? (double)W : slots;
-    double hbm_rate = resident * 1.5 * (t.BM + t.BN) * 128.0 / 2.0;  // bytes/us the workgroups keep in flight
-    if (hbm_rate > 4.5e6) hbm_rate = 4.5e6;
+    double hbm_rate = resident * 1.5 * (t.BM + t.BN) * 128.0 / 1.08;  // bytes/us the workgroups keep in flight
+    if (hbm_rate > 5.63e+06) hbm_rate = 5.63e+06;
+    hbm_rate *= t.hbm_eff;
     const double t_hbm = unique / (hbm_rate * scale[GEMM_COST_HBM]);
-    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / (14.0e6 * scale[GEMM_COST_L2]);
-    double cost = 5.0 * scale[GEMM_COST_FIXED] + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
-    if (S > 1) cost += 4.0 * scale[GEMM_COST_FIXED] + (double)M * N * 4.0 * (double)(S + 1) / (3.0e6 * scale[GEMM_COST_HBM]);
+    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / (1.93e+07 * scale[GEMM_COST_L2]);
+    double cost = 2.54 * scale[GEMM_COST_FIXED] + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
+    if (S > 1)
+        cost += (0.615 + 0.0757 * (double)S) * scale[GEMM_COST_FIXED] +
+                (double)M * N * 4.0 * (double)(S + 1) / (3.79e+06 * scale[GEMM_COST_HBM]);
     return cost;
 }
 
 // max_ws_bytes: largest K-slice workspace the caller can provide (0 = no limit); automatic
 // picks that would need more are not considered.
 // ksplit_ok: the operands qualify for the kernels that split K across the waves of a workgroup
-void choose_uncached(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
-            bool ksplit_ok, int &tile, int &splits)
+void choose_uncached(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int k_contig, int num_cu,
+                     size_t max_ws_bytes, bool ksplit_ok, int &tile, int &splits)
 {
     double best = 1e300;
     tile = g_forced_tile >= 0 ? g_forced_tile : 0;
@@ -234,12 +278,8 @@ void choose_uncached(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int 
         for (int s = 1; s <= 32; s *= 2) {
             const int cand = forced > 0 ? forced : s;
             if (cand > 1 && cand > KT) break;
-            // the rectangular tiles were only ever ahead without K slices (mid-size products)
-            if (g_forced_tile < 0 && forced == 0 && cand > 1 && kTiles[t].BM != kTiles[t].BN) break;
-            if (forced == 0 && cand > 1 && max_ws_bytes > 0 &&
-                (size_t)cand * (size_t)M * (size_t)N * sizeof(float) > max_ws_bytes)
-                break;
-            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, path, num_cu);
+            if (forced == 0 && cand > 1 && max_ws_bytes > 0 && ws_bytes(cand, M, N) > max_ws_bytes) break;
+            const double c = estimate_cost(kTiles[t], M, N, K, KT, cand, f32, path, k_contig, num_cu);
             if (c < best) { best = c; tile = t; splits = cand; }
             if (forced > 0) break;
         }
@@ -253,25 +293,25 @@ struct Pick {
     int64_t M = -1, N = 0, K = 0;
     size_t max_ws = 0;
     uint64_t epoch = 0;
-    int f32 = 0, path = 0, num_cu = 0, ksplit_ok = 0, tile = 0, splits = 0;
+    int f32 = 0, path = 0, k_contig = 0, num_cu = 0, ksplit_ok = 0, tile = 0, splits = 0;
 };
 Pick g_picks[64];
 uint64_t g_epoch = 1;
 
-void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int num_cu, size_t max_ws_bytes,
-            bool ksplit_ok, int &tile, int &splits)
+void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int k_contig, int num_cu,
+            size_t max_ws_bytes, bool ksplit_ok, int &tile, int &splits)
 {
     const uint64_t h = (uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^
-                       (uint64_t)K * 0x165667B19E3779F9ull ^ (uint64_t)(path * 4 + f32 * 2 + ksplit_ok);
+                       (uint64_t)K * 0x165667B19E3779F9ull ^ (uint64_t)(k_contig * 16 + path * 4 + f32 * 2 + ksplit_ok);
     Pick &e = g_picks[(h >> 32) & 63];
     if (e.M == M && e.N == N && e.K == K && e.max_ws == max_ws_bytes && e.epoch == g_epoch && e.f32 == (int)f32 &&
-        e.path == path && e.num_cu == num_cu && e.ksplit_ok == (int)ksplit_ok) {
+        e.path == path && e.k_contig == k_contig && e.num_cu == num_cu && e.ksplit_ok == (int)ksplit_ok) {
         tile = e.tile;
         splits = e.splits;
         return;
     }
-    choose_uncached(M, N, K, KT, f32, path, num_cu, max_ws_bytes, ksplit_ok, tile, splits);
-    e.M = M; e.N = N; e.K = K; e.max_ws = max_ws_bytes; e.epoch = g_epoch; e.f32 = f32; e.path = path;
+    choose_uncached(M, N, K, KT, f32, path, k_contig, num_cu, max_ws_bytes, ksplit_ok, tile, splits);
+    e.M = M; e.N = N; e.K = K; e.max_ws = max_ws_bytes; e.epoch = g_epoch; e.f32 = f32; e.path = path; e.k_contig = k_contig;
     e.num_cu = num_cu; e.ksplit_ok = ksplit_ok; e.tile = tile; e.splits = splits;
 }
 
@@ -416,7 +456,8 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
     const bool ksplit_ok = aligned && !ragged && K % BK == 0;
-    choose(M, N, K, KT, f32, path, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, ksplit_ok, tile, splits);
+    choose(M, N, K, KT, f32, path, (int)akc + (int)bkc, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, ksplit_ok,
+           tile, splits);
     if (kTiles[tile].fallback >= 0 && !ksplit_ok) tile = kTiles[tile].fallback;  // forced, but not served by that kernel
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
@@ -446,7 +487,7 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     a.trace_records = (int)(g_trace_records < (1LL << 30) ? g_trace_records : (1LL << 30));
     void *ws = nullptr;
     if (splits > 1) {
-        const size_t need = (size_t)splits * (size_t)M * (size_t)N * sizeof(float);
+        const size_t need = ws_bytes(splits, M, N);
         int rc;
         if (noalloc) {
             // only a forced configuration can get here with more than the array holds
@@ -457,10 +498,10 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         }
         if (rc != GEMM_OK) return rc;
         a.C = (float *)ws;
-        a.ldc = N;
-        a.split_stride = M * N;
-        // slices are M*N floats from a 256-byte aligned base: rows are on 16-byte boundaries if N % 4 == 0
-        a.rows16_c = (N % 4 == 0 && N < (1LL << 20)) ? 1 : 0;
+        a.ldc = ws_pitch(N);
+        a.split_stride = M * ws_pitch(N);
+        // slices and their rows begin on 128-byte boundaries (256-byte aligned base, padded rows)
+        a.rows16_c = N < (1LL << 20) ? 1 : 0;
         a.stage_c = (a.rows16_c && g_store_mode != 1) ? 1 : 0;
     } else {
         a.C = (float *)C;
@@ -491,16 +532,12 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
         return GEMM_ERR_HIP;
     }
     if (splits > 1) {
-        const int64_t total = M * N;
-        const int64_t items = N % 4 == 0 ? total / 4 : total;
+        const int64_t items = M * cdiv(N, 4);
         const int blocks = (int)(cdiv(items, 256) < 4096 ? cdiv(items, 256) : 4096);
-        // workspace slices are M * N floats each and the workspace is 256-byte aligned, so with
-        // N % 4 == 0 every group of four columns is a 16-byte aligned piece of one row
-        const hipError_t rc =
-            N % 4 == 0 ? launch_kernel(splitk_reduce_kernel<TC, 4>, dim3(blocks), dim3(256), stream, (const float *)ws,
-                                       (int64_t)(M * N), splits, C, ldc, (int)M, (int)N)
-                       : launch_kernel(splitk_reduce_kernel<TC, 1>, dim3(blocks), dim3(256), stream, (const float *)ws,
-                                       (int64_t)(M * N), splits, C, ldc, (int)M, (int)N);
+        const int vec_c = ((uintptr_t)C % (4 * sizeof(TC)) == 0 && ldc % 4 == 0) ? 1 : 0;
+        const hipError_t rc = launch_kernel(splitk_reduce_kernel<TC>, dim3(blocks), dim3(256), stream, (const float *)ws,
+                                            (int64_t)(M * ws_pitch(N)), splits, (int)ws_pitch(N), C, ldc, (int)M, (int)N,
+                                            vec_c);
         if (rc != hipSuccess) return GEMM_ERR_HIP;
     }
     snprintf(t_last_config, sizeof t_last_config, "%s %s %c%c %s s%d%s%s", type_name, t.name,
@@ -548,25 +585,35 @@ int gemm_f16f32_noalloc(int64_t M, int64_t N, int64_t K, const uint16_t *A, int 
     return gemm_impl<_Float16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream, true);
 }
 
-int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen)
+int gemm_query_config_layouts(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, int layoutA, int layoutB,
+                              char *buf, int buflen)
 {
     if ((elem_bytes != 2 && elem_bytes != 4) || M <= 0 || N <= 0 || K <= 0 || !buf || buflen <= 0)
+        return GEMM_ERR_INVALID_ARG;
+    if ((layoutA != GEMM_ROW_MAJOR && layoutA != GEMM_COL_MAJOR) || (layoutB != GEMM_ROW_MAJOR && layoutB != GEMM_COL_MAJOR))
         return GEMM_ERR_INVALID_ARG;
     const bool f32 = elem_bytes == 4;
     const int64_t BK = f32 ? Elem<float>::BK : Elem<_Float16>::BK;
     const int64_t KT = cdiv(K, BK);
+    // K is the contiguous dimension of a row-major A (M x K) and of a column-major B (K x N)
+    const int k_contig = (layoutA == GEMM_ROW_MAJOR ? 1 : 0) + (layoutB == GEMM_COL_MAJOR ? 1 : 0);
     int tile, splits;
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         // 16 or more (or 1): direct loads, aligned; 8 or 4: direct loads on misaligned rows; 0: register-staged
         // (operand extents that are not multiples of the granule); 2: register-staged, 2-byte aligned
         const int path = (aligned == 1 || aligned >= 16) ? 0 : (aligned == 2 ? 2 : (aligned >= 4 ? 3 : 1));
-        choose(M, N, K, KT, f32, path, kDefaultNumCU, 0, (path == 0 || path == 3) && K % BK == 0, tile, splits);
+        choose(M, N, K, KT, f32, path, k_contig, kDefaultNumCU, 0, (path == 0 || path == 3) && K % BK == 0, tile, splits);
     }
     const int64_t per = cdiv(KT, splits);
     splits = (int)cdiv(KT, per);  // no empty slices, as in the launch path
     snprintf(buf, (size_t)buflen, "%s:s%d", kTiles[tile].name, splits);
     return GEMM_OK;
+}
+
+int gemm_query_config(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, char *buf, int buflen)
+{
+    return gemm_query_config_layouts(elem_bytes, M, N, K, aligned, GEMM_ROW_MAJOR, GEMM_ROW_MAJOR, buf, buflen);
 }
 
 int gemm_force_config(const char *name)

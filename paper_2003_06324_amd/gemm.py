@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_query_config_layouts", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -58,6 +58,8 @@ def load_library():
     lib.gemm_cost_model_scale.restype = i32
     lib.gemm_query_config.argtypes = [i32, i64, i64, i64, i32, ctypes.c_char_p, i32]
     lib.gemm_query_config.restype = i32
+    lib.gemm_query_config_layouts.argtypes = [i32, i64, i64, i64, i32, i32, i32, ctypes.c_char_p, i32]
+    lib.gemm_query_config_layouts.restype = i32
     lib.gemm_num_configs.argtypes = []
     lib.gemm_num_configs.restype = i32
     lib.gemm_config_name.argtypes = [i32]
@@ -141,11 +143,17 @@ def set_phase_trace(buffer=None, workgroups=0):
     return _check(load_library().gemm_set_phase_trace(_ptr(buffer), int(workgroups)))
 
 
-def query_config(elem_bytes, M, N, K, aligned=True):
+def query_config(elem_bytes, M, N, K, aligned=True, layout_a=None, layout_b=None):
     """The "<tile>:s<splits>" the selection picks for this shape (host only, nothing is launched).
-    aligned: True / False, or the common alignment of bases and leading dimensions in bytes."""
+    aligned: True / False, or the common alignment of bases and leading dimensions in bytes.
+    layout_a, layout_b: ROW_MAJOR / COL_MAJOR of A (M x K) and B (K x N); both row-major if not given."""
     buf = ctypes.create_string_buffer(64)
-    _check(load_library().gemm_query_config(elem_bytes, M, N, K, int(aligned), buf, 64))
+    lib = load_library()
+    if layout_a is None and layout_b is None:
+        _check(lib.gemm_query_config(elem_bytes, M, N, K, int(aligned), buf, 64))
+    else:
+        _check(lib.gemm_query_config_layouts(elem_bytes, M, N, K, int(aligned), ROW_MAJOR if layout_a is None else layout_a,
+                                             ROW_MAJOR if layout_b is None else layout_b, buf, 64))
     return buf.value.decode()
 
 
