@@ -118,7 +118,11 @@ def phases(launch, iters, what):
         per_cu.append(len(idx))
         gaps += [ts[b, 0] - ts[a, 5] for a, b in zip(idx[:-1], idx[1:])]
     print("  %d CUs used, %d..%d workgroups each" % (len(per_cu), min(per_cu), max(per_cu)))
-    if gaps:
+    if gaps and np.median(gaps) < 0:
+        # a CU runs more than one workgroup of this tile at a time: there is no gap to measure, and
+        # the phases of one workgroup include the time it waits for the matrix cores the other uses
+        print("  workgroups overlap on a CU (next one starts %.1f us before the previous ends, median)" % -np.median(gaps))
+    elif gaps:
         gaps = np.array(gaps)
         print("  %-38s mean %7.2f us   p50 %7.2f   p90 %7.2f   max %7.2f" % (
             "CU idle between two workgroups", gaps.mean(), np.percentile(gaps, 50), np.percentile(gaps, 90), gaps.max()))
