@@ -250,3 +250,47 @@ def test_two_byte_aligned_operands(oracle, dtype):
                         two_byte = any(x % 2 for x in (lda, ldb, offs[0], offs[1]))   # odd element counts
                         assert ("general" in cfg.split()) == two_byte, (cfg, lda, ldb, offs)
                         assert np.array_equal(C, ref), (dtype, M, N, K, la, lb, pads, offs, cfg)
+
+
+@pytest.mark.parametrize("entry", ["f16", "f16f16", "bf16", "f32", "noalloc"])
+def test_k_slices_with_every_residue_of_n(oracle, entry):
+    # Rows of the K-slice workspace are padded to a multiple of 32 floats, so N need not be a multiple
+    # of 4 for the partials and the reduce pass to use 16-byte accesses; the last piece of a row is then
+    # stored element by element, and C itself may have rows that are not 16-byte aligned.  Every N mod 4
+    # (and N below one piece), forced slice counts on a square and a rectangular tile, C with and without
+    # row padding and base offset, and the automatic choice on a deep K (which slices it).
+    import torch
+    import paper_2003_06324_amd as g
+    dtype = {"f16f16": "f16", "noalloc": "f16"}.get(entry, entry)
+    for N in (1, 3, 30, 33, 61, 62, 63, 64, 130):
+        M, K = 70, 9 * 64 + 8
+        A, B = gi.make_problem(700 + N, M, N, K, "int", dtype)
+        if dtype == "bf16":
+            exact = oracle.gemm(M, N, K, gi.bfloat16_bits(A), 0, gi.bfloat16_bits(B), 0, "bf16")
+        else:
+            exact = ref_of(oracle, A, B, dtype)
+        for force in ("t64x64:s3", "t128x64:s4", "t64x128:s2", None):
+            for pads, offs in (((0, 0, 0), (0, 0, 0)), ((0, 0, 3), (0, 0, 1)), ((8, 8, 4), (0, 0, 4))):
+                if entry == "noalloc":
+                    if pads != (0, 0, 0):
+                        continue
+                    dA, dB = (torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda() for x in (A, B))
+                    dC = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+                    g.force_config(force)
+                    try:
+                        g.gemm_f16f32_noalloc(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.ROW_MAJOR, 0, dC, gi.ROW_MAJOR, 0,
+                                              torch.cuda.current_stream().cuda_stream)
+                        cfg = g.last_config()
+                    finally:
+                        g.force_config(None)
+                    torch.cuda.synchronize()
+                    C = dC.cpu().numpy().reshape(M, N)
+                    assert "static-scratch" in cfg, cfg
+                else:
+                    C, cfg = run_gpu(dtype, A, B, gi.ROW_MAJOR, gi.COL_MAJOR, pads=pads, offsets=offs, force=force,
+                                     return_config=True, out="f16" if entry == "f16f16" else "f32")
+                assert int(cfg.split()[4][1:]) > 1, cfg    # K really was cut into slices
+                if entry == "f16f16":
+                    assert np.array_equal(C.view(np.uint16), oracle.round_to_half(exact).view(np.uint16)), (N, force, pads, cfg)
+                else:
+                    assert np.array_equal(C, exact.astype(np.float32)), (entry, N, force, pads, offs, cfg)
