@@ -185,6 +185,33 @@ enum {
 int gemm_cost_model_scale(int term, double factor);
 
 /*
+ * Per-size tuning by measurement (Section 5.3 searches the configurations exhaustively for each
+ * input size and keeps the fastest; the cost model above replaces that search at call time, this
+ * call performs it).  kind names the entry point (GEMM_KIND_*), the other arguments are that entry
+ * point's: the call computes C = A * B like it, then runs the product again with each candidate
+ * (tile, K slices) pair -- the max_candidates cheapest by the cost model, or every pair the library
+ * has if max_candidates is 0 (9 tiles x up to 6 slice counts; about 10 ms for a mid-size shape) --
+ * timing each with events on hip_stream, records the fastest in a process-wide table, computes C
+ * once more with it and writes "<tile>:s<slices>" into buf.  Later calls with the same M, N, K,
+ * operand width (16-bit or binary32), layouts and alignment class on a device with as many CUs use
+ * the recorded pair (so do gemm_query_config*); a forced configuration still overrides it, and
+ * gemm_f16f32_noalloc ignores an entry whose partial sums do not fit its array.  The call blocks the
+ * host until hip_stream has drained, allocates (events, K-slice workspace), and cannot be captured into a
+ * HIP graph.  Errors as the entry point's, plus GEMM_ERR_INVALID_ARG for an unknown kind, a negative
+ * max_candidates or no buffer, and GEMM_ERR_HIP if no candidate could be timed.  An empty product
+ * (M, N or K zero) records nothing and writes "none".  gemm_tune_clear forgets every recorded pair.
+ */
+enum {
+    GEMM_KIND_F32 = 0,     /* gemm_f32 */
+    GEMM_KIND_F16F32 = 1,  /* gemm_f16f32 */
+    GEMM_KIND_F16F16 = 2,  /* gemm_f16f16 */
+    GEMM_KIND_BF16F32 = 3  /* gemm_bf16f32 */
+};
+int gemm_tune(int kind, int64_t M, int64_t N, int64_t K, const void *A, int layoutA, int64_t lda, const void *B, int layoutB,
+              int64_t ldb, void *C, int layoutC, int64_t ldc, void *hip_stream, int max_candidates, char *buf, int buflen);
+int gemm_tune_clear(void);
+
+/*
  * The configuration the selection would pick (or the forced one), without touching the
  * device: elem_bytes is 2 (16-bit operands) or 4 (binary32); aligned is the alignment in
  * bytes that the bases and leading dimensions of A and B share: 16 or more (or 1, "yes")

@@ -4,13 +4,16 @@
 #include "gemm.h"
 #include "gemm_launch.h"
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
 #include <string>
+#include <tuple>
 #include <type_traits>
+#include <utility>
 #include <vector>
 
 using namespace gemm_gfx950;
@@ -298,11 +301,41 @@ struct Pick {
 Pick g_picks[64];
 uint64_t g_epoch = 1;
 
+// Picks found by measurement (gemm_tune): what a call is classified by -> (tile, K slices).  Consulted
+// before the cost model unless a configuration or slice count is forced (g_mutex held).
+struct ShapeKey {
+    int64_t M, N, K;
+    int f32, path, k_contig, num_cu, ksplit_ok;
+    bool operator<(const ShapeKey &o) const
+    {
+        return std::tie(M, N, K, f32, path, k_contig, num_cu, ksplit_ok) <
+               std::tie(o.M, o.N, o.K, o.f32, o.path, o.k_contig, o.num_cu, o.ksplit_ok);
+    }
+};
+std::map<ShapeKey, std::pair<int, int>> g_tuned;
+
+// What gemm_tune passes through a call: a configuration to run instead of the selection's (tile >= 0), and
+// on return the call's classification (filled: the call reached the selection, i.e. it was not empty).
+struct TuneRequest {
+    int tile = -1, splits = 1;
+    ShapeKey key{};
+    bool filled = false;
+};
+
 void choose(int64_t M, int64_t N, int64_t K, int64_t KT, bool f32, int path, int k_contig, int num_cu,
             size_t max_ws_bytes, bool ksplit_ok, int &tile, int &splits)
 {
     const uint64_t h = (uint64_t)M * 0x9E3779B97F4A7C15ull ^ (uint64_t)N * 0xC2B2AE3D27D4EB4Full ^
                        (uint64_t)K * 0x165667B19E3779F9ull ^ (uint64_t)(k_contig * 16 + path * 4 + f32 * 2 + ksplit_ok);
+    if (g_forced_tile < 0 && g_forced_splits == 0 && !g_tuned.empty()) {
+        const auto it = g_tuned.find(ShapeKey{M, N, K, (int)f32, path, k_contig, num_cu, (int)ksplit_ok});
+        if (it != g_tuned.end() && (max_ws_bytes == 0 || it->second.second == 1 ||
+                                    ws_bytes(it->second.second, M, N) <= max_ws_bytes)) {
+            tile = it->second.first;
+            splits = it->second.second;
+            return;
+        }
+    }
     Pick &e = g_picks[(h >> 32) & 63];
     if (e.M == M && e.N == N && e.K == K && e.max_ws == max_ws_bytes && e.epoch == g_epoch && e.f32 == (int)f32 &&
         e.path == path && e.k_contig == k_contig && e.num_cu == num_cu && e.ksplit_ok == (int)ksplit_ok) {
@@ -385,7 +418,8 @@ int static_scratch(DeviceState &d, void **out)
 // noalloc: K-slice partials go to the fixed per-GPU array instead of a grown workspace.
 template <typename T, typename TC>
 int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t lda,
-              const void *B, int layB, int64_t ldb, TC *C, int layC, int64_t ldc, void *stream_, bool noalloc = false)
+              const void *B, int layB, int64_t ldb, TC *C, int layC, int64_t ldc, void *stream_, bool noalloc = false,
+              TuneRequest *tune = nullptr)
 {
     constexpr bool f32 = sizeof(T) == 4;
     constexpr bool out16 = sizeof(TC) == 2;
@@ -456,8 +490,17 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     const int64_t KT = cdiv(K, BK);
     int tile, splits;
     const bool ksplit_ok = aligned && !ragged && K % BK == 0;
-    choose(M, N, K, KT, f32, path, (int)akc + (int)bkc, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0, ksplit_ok,
-           tile, splits);
+    if (tune) {
+        tune->key = ShapeKey{M, N, K, (int)f32, path, (int)akc + (int)bkc, num_cu, (int)ksplit_ok};
+        tune->filled = true;
+    }
+    if (tune && tune->tile >= 0) {
+        tile = tune->tile;
+        splits = (int)(tune->splits < KT ? tune->splits : KT);
+    } else {
+        choose(M, N, K, KT, f32, path, (int)akc + (int)bkc, num_cu, noalloc ? (size_t)GEMM_NOALLOC_SCRATCH_BYTES : 0,
+               ksplit_ok, tile, splits);
+    }
     if (kTiles[tile].fallback >= 0 && !ksplit_ok) tile = kTiles[tile].fallback;  // forced, but not served by that kernel
     const TileConfig &t = kTiles[tile];
     const int64_t tiles_m = cdiv(M, t.BM), tiles_n = cdiv(N, t.BN);
@@ -546,6 +589,86 @@ int gemm_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     return GEMM_OK;
 }
 
+// Per-size tuning by measurement (Section 5.3 searches the configurations exhaustively per input size and
+// keeps the best): runs the call once as it is, then times candidate (tile, K slices) pairs on the caller's
+// operands, stream and device -- the cost model's `max_candidates` cheapest, or all -- and records the fastest
+// for calls that classify alike.  Blocks the host on the stream; C ends up holding the product.
+template <typename T, typename TC>
+int tune_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t lda, const void *B, int layB, int64_t ldb,
+              TC *C, int layC, int64_t ldc, void *stream_, int max_candidates, char *buf, int buflen)
+{
+    if (!buf || buflen <= 0 || max_candidates < 0) return GEMM_ERR_INVALID_ARG;
+    constexpr int BK = Elem<T>::BK;
+    hipStream_t stream = (hipStream_t)stream_;
+    TuneRequest req;
+    int rc = gemm_impl<T, TC>(M, N, K, A, layA, lda, B, layB, ldb, C, layC, ldc, stream_, false, &req);
+    if (rc != GEMM_OK) return rc;
+    if (!req.filled) {  // nothing to multiply
+        snprintf(buf, (size_t)buflen, "none");
+        return GEMM_OK;
+    }
+    const ShapeKey key = req.key;
+    const int64_t KT = cdiv(key.K, BK);
+    std::vector<std::tuple<double, int, int>> cand;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        for (int t = 0; t < kNumTiles; ++t) {
+            if (kTiles[t].fallback >= 0 && !key.ksplit_ok) continue;
+            for (int s = 1; s <= 32 && (s == 1 || s <= KT); s *= 2)
+                cand.emplace_back(estimate_cost(kTiles[t], key.M, key.N, key.K, KT, s, key.f32 != 0, key.path, key.k_contig,
+                                                key.num_cu), t, s);
+        }
+    }
+    std::sort(cand.begin(), cand.end());
+    if (max_candidates > 0 && (size_t)max_candidates < cand.size()) cand.resize((size_t)max_candidates);
+
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
+    }
+    constexpr int kWarm = 2, kTimed = 6;
+    float best_ms = 0.0f;
+    int best_tile = -1, best_splits = 1;
+    rc = GEMM_OK;
+    for (const auto &c : cand) {
+        req.tile = std::get<1>(c);
+        req.splits = std::get<2>(c);
+        bool ok = true;
+        for (int i = 0; i < kWarm + kTimed && ok; ++i) {
+            if (i == kWarm) ok = hipEventRecord(e0, stream) == hipSuccess;
+            ok = ok && gemm_impl<T, TC>(M, N, K, A, layA, lda, B, layB, ldb, C, layC, ldc, stream_, false, &req) == GEMM_OK;
+        }
+        float ms = 0.0f;
+        ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+             hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+        if (!ok) {  // e.g. no memory for this many slices, or a stream under capture: not a candidate
+            (void)hipGetLastError();
+            continue;
+        }
+        if (best_tile < 0 || ms < best_ms) {
+            best_ms = ms;
+            best_tile = req.tile;
+            best_splits = req.splits;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (best_tile < 0) return GEMM_ERR_HIP;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        const int64_t per = cdiv(KT, best_splits);
+        g_tuned[key] = std::make_pair(best_tile, (int)cdiv(KT, per));
+        ++g_epoch;
+    }
+    // the product, by the configuration just recorded (unless one is forced)
+    rc = gemm_impl<T, TC>(M, N, K, A, layA, lda, B, layB, ldb, C, layC, ldc, stream_);
+    const int64_t per = cdiv(KT, best_splits);
+    snprintf(buf, (size_t)buflen, "%s:s%d", kTiles[best_tile].name, (int)cdiv(KT, per));
+    return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -583,6 +706,35 @@ int gemm_f16f32_noalloc(int64_t M, int64_t N, int64_t K, const uint16_t *A, int 
                         void *hip_stream)
 {
     return gemm_impl<_Float16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, hip_stream, true);
+}
+
+int gemm_tune(int kind, int64_t M, int64_t N, int64_t K, const void *A, int layoutA, int64_t lda, const void *B, int layoutB,
+              int64_t ldb, void *C, int layoutC, int64_t ldc, void *hip_stream, int max_candidates, char *buf, int buflen)
+{
+    switch (kind) {
+    case GEMM_KIND_F32:
+        return tune_impl<float, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, (float *)C, layoutC, ldc, hip_stream,
+                                       max_candidates, buf, buflen);
+    case GEMM_KIND_F16F32:
+        return tune_impl<_Float16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, (float *)C, layoutC, ldc, hip_stream,
+                                          max_candidates, buf, buflen);
+    case GEMM_KIND_F16F16:
+        return tune_impl<_Float16, _Float16>(M, N, K, A, layoutA, lda, B, layoutB, ldb, (_Float16 *)C, layoutC, ldc,
+                                             hip_stream, max_candidates, buf, buflen);
+    case GEMM_KIND_BF16F32:
+        return tune_impl<__bf16, float>(M, N, K, A, layoutA, lda, B, layoutB, ldb, (float *)C, layoutC, ldc, hip_stream,
+                                        max_candidates, buf, buflen);
+    default:
+        return GEMM_ERR_INVALID_ARG;
+    }
+}
+
+int gemm_tune_clear(void)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_tuned.clear();
+    ++g_epoch;
+    return GEMM_OK;
 }
 
 int gemm_query_config_layouts(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, int layoutA, int layoutB,

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_query_config_layouts", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_query_config_layouts", "gemm_tune", "gemm_tune_clear", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -60,6 +60,11 @@ def load_library():
     lib.gemm_query_config.restype = i32
     lib.gemm_query_config_layouts.argtypes = [i32, i64, i64, i64, i32, i32, i32, ctypes.c_char_p, i32]
     lib.gemm_query_config_layouts.restype = i32
+    lib.gemm_tune.argtypes = [i32, i64, i64, i64, ctypes.c_void_p, i32, i64, ctypes.c_void_p, i32, i64, ctypes.c_void_p, i32, i64,
+                              ctypes.c_void_p, i32, ctypes.c_char_p, i32]
+    lib.gemm_tune.restype = i32
+    lib.gemm_tune_clear.argtypes = []
+    lib.gemm_tune_clear.restype = i32
     lib.gemm_num_configs.argtypes = []
     lib.gemm_num_configs.restype = i32
     lib.gemm_config_name.argtypes = [i32]
@@ -141,6 +146,26 @@ def set_phase_trace(buffer=None, workgroups=0):
     """Device buffer of 8 * workgroups uint64 that the kernels fill with per-workgroup phase
     timestamps (see include/gemm.h); None switches the trace off."""
     return _check(load_library().gemm_set_phase_trace(_ptr(buffer), int(workgroups)))
+
+
+KIND_F32, KIND_F16F32, KIND_F16F16, KIND_BF16F32 = 0, 1, 2, 3
+
+
+def tune(kind, M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, stream=None, max_candidates=0, check=True):
+    """Times the candidate configurations for this call (kind: KIND_*, the other arguments as that entry point's),
+    records the fastest for later calls of the same class and returns it as "<tile>:s<slices>".  Blocks the host.
+    With check=False returns (status, text)."""
+    buf = ctypes.create_string_buffer(64)
+    rc = load_library().gemm_tune(kind, M, N, K, _ptr(A), layoutA, lda, _ptr(B), layoutB, ldb, _ptr(C), layoutC, ldc,
+                                  stream or None, max_candidates, buf, 64)
+    if check:
+        _check(rc)
+        return buf.value.decode()
+    return rc, buf.value.decode()
+
+
+def tune_clear():
+    return _check(load_library().gemm_tune_clear())
 
 
 def query_config(elem_bytes, M, N, K, aligned=True, layout_a=None, layout_b=None):

@@ -111,6 +111,19 @@ def test_selection_of_tile_and_k_slices():
     assert g.load_library().gemm_query_config(3, 1, 1, 1, 1, None, 0) == -1
 
 
+def test_tune_argument_checks_need_no_device():
+    """gemm_tune refuses an unknown kind, a missing buffer or a negative candidate count before it touches
+    the device; gemm_tune_clear is host-only."""
+    import ctypes
+    import paper_2003_06324_amd as g
+    buf = ctypes.create_string_buffer(16)
+    lib = g.load_library()
+    assert lib.gemm_tune(17, 4, 4, 4, None, 0, 0, None, 0, 0, None, 0, 0, None, 0, buf, 16) == -1
+    assert lib.gemm_tune(g.KIND_F16F32, 4, 4, 4, None, 0, 0, None, 0, 0, None, 0, 0, None, 0, None, 0) == -1
+    assert lib.gemm_tune(g.KIND_F16F32, 4, 4, 4, None, 0, 0, None, 0, 0, None, 0, 0, None, -2, buf, 16) == -1
+    g.tune_clear()
+
+
 def test_header_is_plain_c():
     """include/gemm.h must be usable from C: no C++ or HIP types in the boundary."""
     import subprocess
