@@ -212,6 +212,18 @@ int gemm_tune(int kind, int64_t M, int64_t N, int64_t K, const void *A, int layo
 int gemm_tune_clear(void);
 
 /*
+ * The recorded pairs as a text file, so that a service tunes once and later processes start with the picks:
+ * gemm_tune_save writes every pair gemm_tune has recorded (one line each: bytes per operand element, M, N,
+ * K, alignment class, number of K-contiguous operands, CU count, whether the operands are whole slabs and
+ * granules, tile name, K slices; '#' starts a comment line); gemm_tune_load adds the pairs of such a file to
+ * the table, replacing entries for the same class.  Host only.  GEMM_ERR_INVALID_ARG if the file cannot be
+ * opened or written, or (load) if any line does not parse, names a tile this build does not have or one
+ * that cannot serve the line's class: then nothing of the file is taken over.
+ */
+int gemm_tune_save(const char *path);
+int gemm_tune_load(const char *path);
+
+/*
  * The configuration the selection would pick (or the forced one), without touching the
  * device: elem_bytes is 2 (16-bit operands) or 4 (binary32); aligned is the alignment in
  * bytes that the bases and leading dimensions of A and B share: 16 or more (or 1, "yes")

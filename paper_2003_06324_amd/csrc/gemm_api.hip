@@ -737,6 +737,60 @@ int gemm_tune_clear(void)
     return GEMM_OK;
 }
 
+// One recorded pick per line: "<bytes per operand element> M N K <alignment class> <K-contiguous operands> <CUs>
+// <whole slabs and granules> <tile> <K slices>"; lines starting with '#' are comments.
+int gemm_tune_save(const char *path)
+{
+    if (path == nullptr) return GEMM_ERR_INVALID_ARG;
+    FILE *f = fopen(path, "w");
+    if (f == nullptr) return GEMM_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    fprintf(f, "# gemm_tune picks: elem_bytes M N K class k_contig cus whole tile slices\n");
+    for (const auto &e : g_tuned) {
+        const ShapeKey &k = e.first;
+        fprintf(f, "%d %lld %lld %lld %d %d %d %d %s %d\n", k.f32 ? 4 : 2, (long long)k.M, (long long)k.N, (long long)k.K, k.path,
+                k.k_contig, k.num_cu, k.ksplit_ok, kTiles[e.second.first].name, e.second.second);
+    }
+    return fclose(f) == 0 ? GEMM_OK : GEMM_ERR_INVALID_ARG;
+}
+
+int gemm_tune_load(const char *path)
+{
+    if (path == nullptr) return GEMM_ERR_INVALID_ARG;
+    FILE *f = fopen(path, "r");
+    if (f == nullptr) return GEMM_ERR_INVALID_ARG;
+    std::map<ShapeKey, std::pair<int, int>> read;
+    char line[256];
+    int rc = GEMM_OK;
+    while (rc == GEMM_OK && fgets(line, sizeof line, f) != nullptr) {
+        if (line[0] == '#' || line[0] == '\n' || line[0] == 0) continue;
+        long long M, N, K;
+        int esz, path_, kc, cus, whole, slices;
+        char name[32];
+        if (sscanf(line, "%d %lld %lld %lld %d %d %d %d %31s %d", &esz, &M, &N, &K, &path_, &kc, &cus, &whole, name, &slices) != 10 ||
+            (esz != 2 && esz != 4) || M <= 0 || N <= 0 || K <= 0 || path_ < 0 || path_ > 3 || kc < 0 || kc > 2 || cus <= 0 ||
+            (whole != 0 && whole != 1) || slices < 1 || slices > 1024) {
+            rc = GEMM_ERR_INVALID_ARG;
+            break;
+        }
+        int tile = -1;
+        for (int i = 0; i < kNumTiles; ++i)
+            if (strcmp(name, kTiles[i].name) == 0) tile = i;
+        // a tile this build does not have, or one that does not serve the class, makes the file invalid as a whole
+        if (tile < 0 || (kTiles[tile].fallback >= 0 && !whole)) {
+            rc = GEMM_ERR_INVALID_ARG;
+            break;
+        }
+        read[ShapeKey{M, N, K, esz == 4, path_, kc, cus, whole}] = std::make_pair(tile, slices);
+    }
+    fclose(f);
+    if (rc != GEMM_OK) return rc;   // nothing of a bad file is taken over
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (const auto &e : read) g_tuned[e.first] = e.second;
+    ++g_epoch;
+    return GEMM_OK;
+}
+
 int gemm_query_config_layouts(int elem_bytes, int64_t M, int64_t N, int64_t K, int aligned, int layoutA, int layoutB,
                               char *buf, int buflen)
 {

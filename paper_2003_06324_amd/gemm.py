@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgemm_mi355x.so")
 _lib = None
 
-EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_query_config_layouts", "gemm_tune", "gemm_tune_clear", "gemm_num_configs", "gemm_config_name",
+EXPORTS = ("gemm_f32", "gemm_f16f32", "gemm_f16f16", "gemm_bf16f32", "gemm_f16f32_noalloc", "gemm_cost_model_scale", "gemm_set_phase_trace", "gemm_force_config", "gemm_query_config", "gemm_query_config_layouts", "gemm_tune", "gemm_tune_clear", "gemm_tune_save", "gemm_tune_load", "gemm_num_configs", "gemm_config_name",
            "gemm_last_config", "gemm_status_string", "gemm_shutdown")
 
 
@@ -65,6 +65,10 @@ def load_library():
     lib.gemm_tune.restype = i32
     lib.gemm_tune_clear.argtypes = []
     lib.gemm_tune_clear.restype = i32
+    lib.gemm_tune_save.argtypes = [ctypes.c_char_p]
+    lib.gemm_tune_save.restype = i32
+    lib.gemm_tune_load.argtypes = [ctypes.c_char_p]
+    lib.gemm_tune_load.restype = i32
     lib.gemm_num_configs.argtypes = []
     lib.gemm_num_configs.restype = i32
     lib.gemm_config_name.argtypes = [i32]
@@ -166,6 +170,18 @@ def tune(kind, M, N, K, A, layoutA, lda, B, layoutB, ldb, C, layoutC, ldc, strea
 
 def tune_clear():
     return _check(load_library().gemm_tune_clear())
+
+
+def tune_save(path, check=True):
+    """Writes the picks gemm_tune has recorded to a text file."""
+    rc = load_library().gemm_tune_save(str(path).encode())
+    return _check(rc) if check else rc
+
+
+def tune_load(path, check=True):
+    """Adds the picks of a file written by tune_save to the table."""
+    rc = load_library().gemm_tune_load(str(path).encode())
+    return _check(rc) if check else rc
 
 
 def query_config(elem_bytes, M, N, K, aligned=True, layout_a=None, layout_b=None):

@@ -124,6 +124,50 @@ def test_tune_argument_checks_need_no_device():
     g.tune_clear()
 
 
+def test_recorded_picks_load_from_a_file_and_precede_the_cost_model(tmp_path):
+    """The table gemm_tune fills can be saved and loaded as text; a loaded pick answers for its class (and only
+    for it) before the cost model does, a forced configuration still wins, and a bad file changes nothing."""
+    import paper_2003_06324_amd as g
+    g.force_config(None)
+    g.tune_clear()
+    f = tmp_path / "picks.txt"
+    try:
+        model = g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR)
+        assert model == "t128x128:s1"
+        f.write_text("# comment\n2 2048 2048 2048 0 2 256 1 t64x128 4\n4 300 200 100 3 1 256 0 t256x256w8 2\n")
+        g.tune_load(f)
+        assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR) == "t64x128:s4"
+        assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.ROW_MAJOR) == model       # other layouts: other class
+        assert g.query_config(2, 2048, 2048, 2048, 4, g.ROW_MAJOR, g.COL_MAJOR) != "t64x128:s4"  # other alignment class
+        assert g.query_config(4, 300, 200, 100, 4, g.ROW_MAJOR, g.ROW_MAJOR) == "t256x256w8:s2"
+        g.force_config("t128x64:s2")
+        assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR) == "t128x64:s2"
+        g.force_config(None)
+        # round trip
+        out = tmp_path / "saved.txt"
+        g.tune_save(out)
+        lines = [ln for ln in out.read_text().split("\n") if ln and not ln.startswith("#")]
+        assert sorted(lines) == ["2 2048 2048 2048 0 2 256 1 t64x128 4", "4 300 200 100 3 1 256 0 t256x256w8 2"]
+        g.tune_clear()
+        assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR) == model
+        g.tune_load(out)
+        assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR) == "t64x128:s4"
+        # files that do not parse, name an unknown tile, or give the K-split-across-waves tile a class it does not
+        # serve are refused as a whole
+        g.tune_clear()
+        for text in ("2 2048 2048 2048 0 2 256 1 t64x128\n", "2 64 64 64 0 2 256 1 t1x1 1\n", "3 64 64 64 0 2 256 1 t64x64 1\n",
+                     "2 512 512 512 0 2 256 1 t64x64 1\n2 64 64 100 0 2 256 0 k64x64 1\n", "2 64 64 64 7 2 256 1 t64x64 1\n"):
+            f.write_text(text)
+            assert g.tune_load(f, check=False) == -1, text
+        out2 = tmp_path / "empty.txt"
+        g.tune_save(out2)
+        assert [ln for ln in out2.read_text().split("\n") if ln and not ln.startswith("#")] == []
+        assert g.tune_load(tmp_path / "missing.txt", check=False) == -1
+    finally:
+        g.force_config(None)
+        g.tune_clear()
+
+
 def test_header_is_plain_c():
     """include/gemm.h must be usable from C: no C++ or HIP types in the boundary."""
     import subprocess

@@ -16,7 +16,7 @@ def _problem(oracle, dtype, M, N, K, seed):
 
 
 @pytest.mark.parametrize("dtype,kind_name", [("f16", "KIND_F16F32"), ("f32", "KIND_F32")])
-def test_tune_records_the_measured_pick_and_calls_use_it(oracle, dtype, kind_name):
+def test_tune_records_the_measured_pick_and_calls_use_it(oracle, dtype, kind_name, tmp_path):
     import torch
     import paper_2003_06324_amd as g
     kind = getattr(g, kind_name)
@@ -50,6 +50,14 @@ def test_tune_records_the_measured_pick_and_calls_use_it(oracle, dtype, kind_nam
         g.tune_clear()
         assert g.query_config(elem, M, N, K, 16, gi.ROW_MAJOR, gi.COL_MAJOR) != pick
         g.cost_model_scale(-1)
+        # saved and loaded again, the pick serves the next process's calls
+        pick = g.tune(kind, M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, stream)
+        g.tune_save(tmp_path / "picks.txt")
+        g.tune_clear()
+        g.tune_load(tmp_path / "picks.txt")
+        call(M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, stream)
+        cfg = g.last_config().split()
+        assert cfg[1] + ":" + cfg[4] == pick, (cfg, pick)
         # a forced configuration overrides a recorded pick
         pick = g.tune(kind, M, N, K, dA, gi.ROW_MAJOR, 0, dB, gi.COL_MAJOR, 0, dC, gi.ROW_MAJOR, 0, stream, max_candidates=3)
         g.force_config("t128x128:s2")
