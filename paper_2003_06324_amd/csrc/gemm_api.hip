@@ -5,6 +5,7 @@
 #include "gemm_launch.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -152,24 +153,24 @@ struct TileConfig {
 // by load latency, not by its MFMA work) and are not clock-peak figures.
 // (64x128 before 128x64: the model often ties the two, and the tie goes to the first; 64x128 measures 4-8 % ahead)
 const TileConfig kTiles[] = {
-    {"t256x256", 256, 256, 1, 1.1, 1.1, 7.56, 7.56, 5.15, 0.747, 1.01, 0.969, 2.11, 1.25, 1,
+    {"t256x256", 256, 256, 1, 1.02, 1.02, 6.98, 6.98, 7.2, 0.83, 1.2, 1.05, 1.67, 1.25, 1,
      GEMM_TILE_LAUNCHERS(256, 256, 2, 2), -1, 15, 15},
-    {"t128x128", 128, 128, 2, 0.505, 0.847, 1.88, 3.26, 1.46, 1.31, 1.16, 0.979, 1.62, 1.3, 3,
+    {"t128x128", 128, 128, 2, 0.457, 0.868, 1.99, 3.64, 1.92, 1.39, 1.23, 0.817, 1.57, 1.3, 3,
      GEMM_TILE_LAUNCHERS(128, 128, 2, 2), -1, 15, 15},
-    {"t64x64", 64, 64, 4, 0.281, 0.72, 0.484, 1.71, 1.21, 0.862, 1.1, 0.995, 1.48, 1.35, 4,
+    {"t64x64", 64, 64, 4, 0.265, 0.855, 0.495, 1.86, 1.27, 0.78, 1.07, 0.992, 1.65, 1.35, 4,
      GEMM_TILE_LAUNCHERS(64, 64, 2, 2), -1, 15, 15},
-    {"t256x256w8", 256, 256, 1, 1.15, 1.15, 6.99, 6.99, 3.35, 0.681, 1.02, 1.01, 1.21, 1.15, 1,
+    {"t256x256w8", 256, 256, 1, 1.05, 1.05, 7.6, 7.6, 6.02, 0.812, 1.2, 0.915, 1.35, 1.15, 1,
      GEMM_TILE_LAUNCHERS(256, 256, 2, 4), -1, 15, 15},
-    {"t256x128", 256, 128, 1, 0.83, 0.83, 3.58, 3.58, 2.97, 1.2, 1.1, 0.963, 1.54, 1.3, 1,
+    {"t256x128", 256, 128, 1, 0.71, 0.71, 3.52, 3.52, 3.82, 0.637, 1.2, 1.09, 1.47, 1.3, 1,
      GEMM_TILE_LAUNCHERS(256, 128, 2, 2), -1, 15, 15},
-    {"t128x256", 128, 256, 1, 0.725, 0.725, 3.36, 3.36, 3.12, 1.29, 1.09, 1.11, 1.88, 1.3, 1,
+    {"t128x256", 128, 256, 1, 0.661, 0.661, 4.19, 4.19, 4.17, 1.78, 1.25, 0.864, 2.03, 1.3, 1,
      GEMM_TILE_LAUNCHERS(128, 256, 2, 2), -1, 15, 15},
-    {"t64x128", 64, 128, 2, 0.362, 0.593, 0.889, 1.7, 1.42, 0.954, 1.26, 0.996, 1.62, 1.3, 3,
+    {"t64x128", 64, 128, 2, 0.349, 0.512, 1.12, 1.86, 1.67, 1.11, 1.31, 0.884, 1.87, 1.3, 3,
      GEMM_TILE_LAUNCHERS(64, 128, 2, 2), -1, 15, 15},
-    {"t128x64", 128, 64, 2, 0.367, 0.595, 0.965, 1.65, 1.34, 0.919, 1.32, 1.03, 1.73, 1.3, 3,
+    {"t128x64", 128, 64, 2, 0.371, 0.617, 1.14, 1.81, 1.33, 1.06, 1.31, 0.919, 1.84, 1.3, 3,
      GEMM_TILE_LAUNCHERS(128, 64, 2, 2), -1, 15, 15},
     // K split across the four waves of the workgroup (Section 5.3, small sizes); fitted on 16-byte aligned operands only
-    {"k64x64", 64, 64, 4, 0.29, 0.712, 0.545, 1.83, 2.32, 0.856, 1.1, 0.995, 1.48, 1.0, 1,
+    {"k64x64", 64, 64, 4, 0.311, 0.854, 0.598, 2.02, 2.02, 0.781, 1.07, 0.992, 1.65, 1.0, 1,
      launch_ksplit<_Float16, 64, 64>, launch_ksplit<float, 64, 64>, launch_ksplit<__bf16, 64, 64>, 2, 1, 1},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
@@ -220,8 +221,8 @@ size_t ws_bytes(int64_t splits, int64_t M, int64_t N) { return (size_t)splits * 
 double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64_t KT, int splits, bool f32,
                      int path, int k_contig, int NUM_CU)
 {
-    static const double kLayA4[3] = {0.881, 1.0, 0.86};  // 16-bit, path 3, by k_contig
-    static const double kLayA2[3] = {0.884, 1.0, 1.2};   // 16-bit, path 2
+    static const double kLayA4[3] = {0.867, 1.0, 0.986};  // 16-bit, path 3, by k_contig
+    static const double kLayA2[3] = {1.14, 1.0, 1.19};   // 16-bit, path 2
     const double *const scale = g_cost_scale;
     const int64_t tiles = cdiv(M, t.BM) * cdiv(N, t.BN);
     const int64_t per = cdiv(KT, splits);
@@ -232,34 +233,42 @@ double estimate_cost(const TileConfig &t, int64_t M, int64_t N, int64_t K, int64
     const int64_t share = cdiv(W, NUM_CU) < t.wg_per_cu ? cdiv(W, NUM_CU) : t.wg_per_cu;
     const double alone = f32 ? t.f32_alone : t.f16_alone, full = f32 ? t.f32_full : t.f16_full;
     double slab = alone + (t.wg_per_cu > 1 ? (full - alone) * (double)(share - 1) / (t.wg_per_cu - 1) : 0.0);
+    const double esz = f32 ? 4.0 : 2.0;
+    // Operands small enough to stay in the XCDs' L2s between and within calls are served faster than ones that come
+    // from the memory side: the slab time falls, log-linearly in the bytes of A and B, from 1 x at kFootHi bytes to
+    // kFootFactor x at kFootLo bytes and below (fitted on the paper's power-of-two sizes, where it decides between
+    // one slice and several for the sizes up to 1024).
+    static const double kFootLo = 2.23e+05, kFootHi = 1.52e+07, kFootFactor = 0.29;
+    const double foot = ((double)M * K + (double)K * N) * esz;
+    const double foot_factor = foot <= kFootLo ? kFootFactor
+                               : (foot >= kFootHi ? 1.0 : exp(log(kFootFactor) * (log(kFootHi) - log(foot)) / (log(kFootHi) - log(kFootLo))));
     // slabs' worth of extra time for the guarded last slab of a ragged K
-    double tail = f32 ? (path == 3 ? 1.88 : 1.44) : (path == 3 ? 2.55 : 2.54);
-    if (path == 3) {
-        slab *= f32 ? t.f32_a4 : t.f16_a4 * kLayA4[k_contig];
-    } else if (path != 0) {
+    double tail = f32 ? (path == 3 ? 3.23 : 1.27) : (path == 3 ? 2.8 : 2.32);
+    if (path == 3) slab *= f32 ? t.f32_a4 : t.f16_a4 * kLayA4[k_contig];
+    if (path == 1 || path == 2) slab *= f32 ? 1.05 : (path == 2 ? t.f16_a2 * kLayA2[k_contig] : t.general);
+    slab *= foot_factor;
+    if (path == 1 || path == 2) {
         // the register-staged path keeps `depth` slabs in flight per workgroup: a slab cannot take
         // less than that share of a global-load round trip
         // (binary32 slabs are bound by their MFMA time: measured within 5 % of the direct path)
-        slab *= f32 ? 1.05 : (path == 2 ? t.f16_a2 * kLayA2[k_contig] : t.general);
         const double floor = 1.2 / ((double)share * t.depth);
         if (slab < floor) slab = floor;
-        if (!f32) tail = 3.77;
+        if (!f32) tail = 4.58;
     }
     slab *= scale[GEMM_COST_SLAB];
     double t_mfma = rounds * ((double)per * slab + t.fixed);
     if (K % (f32 ? 32 : 64) != 0) t_mfma += tail * slab;
-    const double esz = f32 ? 4.0 : 2.0;
     const double unique = ((double)M * K + (double)K * N) * esz + (double)M * N * 4.0;
     const double resident = (double)W < slots ? (double)W : slots;
-    double hbm_rate = resident * 1.5 * (t.BM + t.BN) * 128.0 / 1.08;  // bytes/us the workgroups keep in flight
-    if (hbm_rate > 5.63e+06) hbm_rate = 5.63e+06;
+    double hbm_rate = resident * 1.5 * (t.BM + t.BN) * 128.0 / 0.848;  // bytes/us the workgroups keep in flight
+    if (hbm_rate > 4.79e+06) hbm_rate = 4.79e+06;
     hbm_rate *= t.hbm_eff;
     const double t_hbm = unique / (hbm_rate * scale[GEMM_COST_HBM]);
-    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / (1.93e+07 * scale[GEMM_COST_L2]);
-    double cost = 2.54 * scale[GEMM_COST_FIXED] + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
+    const double t_l2 = (double)W * (double)per * (t.BM + t.BN) * 128.0 / (2.18e+07 * scale[GEMM_COST_L2]);
+    double cost = 2.68 * scale[GEMM_COST_FIXED] + (t_mfma > t_hbm ? (t_mfma > t_l2 ? t_mfma : t_l2) : (t_hbm > t_l2 ? t_hbm : t_l2));
     if (S > 1)
-        cost += (0.615 + 0.0757 * (double)S) * scale[GEMM_COST_FIXED] +
-                (double)M * N * 4.0 * (double)(S + 1) / (3.79e+06 * scale[GEMM_COST_HBM]);
+        cost += (1.51 + 0.0868 * (double)S) * scale[GEMM_COST_FIXED] +
+                (double)M * N * 4.0 * (double)(S + 1) / (3.8e+06 * scale[GEMM_COST_HBM]);
     return cost;
 }
 
@@ -622,39 +631,55 @@ int tune_impl(int64_t M, int64_t N, int64_t K, const void *A, int layA, int64_t 
     std::sort(cand.begin(), cand.end());
     if (max_candidates > 0 && (size_t)max_candidates < cand.size()) cand.resize((size_t)max_candidates);
 
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
-        if (e0) (void)hipEventDestroy(e0);
-        (void)hipGetLastError();
-        return GEMM_ERR_HIP;
+    // One pass: every candidate of `list` gets `warm` untimed and `timed` timed launches between two events of its
+    // own; everything is enqueued back to back and the host waits once at the end, so the GPU never idles between
+    // candidates (it lowers its clock within microseconds of idling, and the next candidate would be timed slow).
+    // Returns (milliseconds per launch, tile, slices) of the candidates that ran.
+    typedef std::vector<std::tuple<float, int, int>> timing_list;
+    auto pass = [&](const timing_list &list, int warm, int timed, timing_list &out) {
+        std::vector<hipEvent_t> ev(2 * list.size(), nullptr);
+        std::vector<char> ran(list.size(), 0);
+        bool events_ok = true;
+        for (auto &e : ev) events_ok = events_ok && hipEventCreate(&e) == hipSuccess;
+        for (size_t c = 0; events_ok && c < list.size(); ++c) {
+            req.tile = std::get<1>(list[c]);
+            req.splits = std::get<2>(list[c]);
+            bool ok = true;
+            for (int i = 0; i < warm + timed && ok; ++i) {
+                if (i == warm) ok = hipEventRecord(ev[2 * c], stream) == hipSuccess;
+                ok = ok && gemm_impl<T, TC>(M, N, K, A, layA, lda, B, layB, ldb, C, layC, ldc, stream_, false, &req) == GEMM_OK;
+            }
+            ran[c] = ok && hipEventRecord(ev[2 * c + 1], stream) == hipSuccess;
+        }
+        if (events_ok) events_ok = hipStreamSynchronize(stream) == hipSuccess;
+        for (size_t c = 0; events_ok && c < list.size(); ++c) {
+            float ms = 0.0f;
+            if (ran[c] && hipEventElapsedTime(&ms, ev[2 * c], ev[2 * c + 1]) == hipSuccess)
+                out.emplace_back(ms / (float)timed, std::get<1>(list[c]), std::get<2>(list[c]));
+        }
+        for (auto &e : ev)
+            if (e) (void)hipEventDestroy(e);
+        (void)hipGetLastError();   // e.g. a candidate with no memory for its slices, or a stream under capture
+    };
+    timing_list all, first, second;
+    for (const auto &c : cand) all.emplace_back(0.0f, std::get<1>(c), std::get<2>(c));
+    // 40 untimed launches of the cheapest candidate first: the part raises its clock over the first tens of
+    // microseconds of work, and the model's favourites are timed first.  Then six timed launches per candidate,
+    // then the four fastest again with 24: short kernels time +-20 % on six launches.
+    {
+        timing_list warmup(1, all[0]), ignored;
+        pass(warmup, 0, 40, ignored);
     }
-    constexpr int kWarm = 2, kTimed = 6;
-    float best_ms = 0.0f;
+    pass(all, 2, 6, first);
+    std::sort(first.begin(), first.end());
+    if (first.size() > 4) first.resize(4);
+    pass(first, 3, 24, second);
+    std::sort(second.begin(), second.end());
     int best_tile = -1, best_splits = 1;
-    rc = GEMM_OK;
-    for (const auto &c : cand) {
-        req.tile = std::get<1>(c);
-        req.splits = std::get<2>(c);
-        bool ok = true;
-        for (int i = 0; i < kWarm + kTimed && ok; ++i) {
-            if (i == kWarm) ok = hipEventRecord(e0, stream) == hipSuccess;
-            ok = ok && gemm_impl<T, TC>(M, N, K, A, layA, lda, B, layB, ldb, C, layC, ldc, stream_, false, &req) == GEMM_OK;
-        }
-        float ms = 0.0f;
-        ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
-             hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
-        if (!ok) {  // e.g. no memory for this many slices, or a stream under capture: not a candidate
-            (void)hipGetLastError();
-            continue;
-        }
-        if (best_tile < 0 || ms < best_ms) {
-            best_ms = ms;
-            best_tile = req.tile;
-            best_splits = req.splits;
-        }
+    if (!second.empty()) {
+        best_tile = std::get<1>(second[0]);
+        best_splits = std::get<2>(second[0]);
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     if (best_tile < 0) return GEMM_ERR_HIP;
     {
         std::lock_guard<std::mutex> lock(g_mutex);

@@ -6,16 +6,16 @@ done once: `tune_sweep.py --all` times every configuration at 1..32 K slices on 
 and this script fits the model to those logs.
 
     python3 -m paper_2003_06324_amd.tune_sweep --all --shapes-file paper_2003_06324_amd/tune_shapes/fit_a.txt > a.log
-    ... (fit_b.txt, fit_c.txt, and the built-in shapes: tune_sweep --all > tuned.log)
-    python3 -m paper_2003_06324_amd.fit_cost_model --tuned tuned.log a.log b.log c.log
+    ... (fit_b.txt, fit_c.txt, paper_ranges.txt, and the built-in shapes: tune_sweep --all > tuned.log)
+    python3 -m paper_2003_06324_amd.fit_cost_model --tuned tuned.log --paper paper.log a.log b.log c.log
 
 Two steps per operand class (binary16 / binary32 x aligned / 4-byte aligned / 2-byte aligned):
 least squares on log(predicted / measured) over all configurations of all shapes, then a random
 search that lowers the time lost by the model's pick against the best measured configuration
-(geometric mean and worst case over the random shapes, more weight on the built-in shapes, which
-are the benchmark configurations, and on the same picks with each of the four run-time scale
-factors of the model at 0.88 and 1.12).  A microsecond is added to both times of a ratio: the
-few-microsecond shapes time +-20 % from run to run.  The script prints the table rows and constants
+(geometric mean and worst case over the random shapes and, as a group of its own, over the paper's
+power-of-two sizes; more weight on the built-in shapes, which are the benchmark configurations,
+and on the same picks with each of the four run-time scale factors of the model at 0.88 and 1.12).
+A microsecond is added to both times of a ratio: the few-microsecond shapes time +-20 % from run to run.  The script prints the table rows and constants
 to carry into gemm_api.hip by hand; tune_shapes/validation.txt is never passed to it.
 
 This file mirrors the model's formula; tests/test_cabi_exports.py checks the library's picks, not
@@ -36,7 +36,8 @@ TILES = {"t256x256": (256, 256, 1, 1), "t128x128": (128, 128, 2, 3), "t64x64": (
 NAMES = list(TILES)
 PATH_OF_CLASS = {"aligned": 0, "aligned4": 3, "general": 2}
 K_CONTIG = {"NN": 1, "NT": 2, "TN": 0, "TT": 1}     # how many of A, B have K as their contiguous dimension
-GLOBALS = dict(fixed=2.5, lat=1.1, hbm_cap=5.6e6, l2=19e6, red_fixed=0.6, red_rate=3.8e6, red_slice=0.08)
+GLOBALS = dict(fixed=2.7, lat=0.85, hbm_cap=4.8e6, l2=22e6, red_fixed=1.5, red_rate=3.8e6, red_slice=0.087,
+               foot_factor=0.29, foot_lo=2.2e5, foot_hi=1.5e7)
 GLOBAL_NAMES = list(GLOBALS)
 # starting points: (alone, full, fixed) per 64-k binary16 slab, (alone, full) per 32-k binary32 slab
 START16 = {"t256x256": (1.1, 1.1, 5.0), "t128x128": (0.5, 0.85, 1.5), "t64x64": (0.28, 0.72, 1.2), "t256x256w8": (1.15, 1.15, 3.4),
@@ -87,6 +88,12 @@ def cost(tile, alone, full, fixed, hbm_eff, G, sh, splits, esz, mult=1.0, floor_
     share = min(cdiv(W, NUM_CU), occ)
     slab = alone + ((full - alone) * (share - 1) / (occ - 1) if occ > 1 else 0.0)
     slab *= mult * lay[K_CONTIG[sh["lay"]]]
+    foot = (M * K + K * N) * esz      # operands that stay in the L2s are served faster
+    if foot <= G["foot_lo"]:
+        slab *= G["foot_factor"]
+    elif foot < G["foot_hi"]:
+        slab *= math.exp(math.log(G["foot_factor"]) * (math.log(G["foot_hi"]) - math.log(foot)) /
+                         (math.log(G["foot_hi"]) - math.log(G["foot_lo"])))
     if floor_lat:
         slab = max(slab, floor_lat / (share * depth))
     slab *= sc[0]
@@ -137,23 +144,28 @@ def summary(r):
     return "n %d geomean %.3f p90 %.2f max %.2f" % (len(r), math.exp(np.log(r).mean()), np.quantile(r, .9), r.max()) if len(r) else "n 0"
 
 
-def objective(rand, tuned, cf):
-    r = np.log(regret(rand, cf))
-    u = np.log(regret(tuned, cf)) if tuned else np.zeros(1)
-    j = r.mean() + 0.15 * r.max() + 3.0 * u.mean() + 1.0 * u.max()
-    for sc in PERTURBED if tuned else ():
-        j += 0.5 * np.log(regret(tuned, lambda sh, t, s: cf(sh, t, s, sc))).max()
+def objective(groups, tuned, cf):
+    j = 0.0
+    for shapes in groups:
+        if shapes:
+            r = np.log(regret(shapes, cf))
+            j += r.mean() + 0.15 * r.max()
+    if tuned:
+        u = np.log(regret(tuned, cf))
+        j += 4.0 * u.mean() + 3.0 * u.max()
+        for sc in PERTURBED:
+            j += 0.5 * np.log(regret(tuned, lambda sh, t, s: cf(sh, t, s, sc))).max()
     return j
 
 
-def refine(x, make_cf, rand, tuned, iters, seed=0, sigma=0.05):
+def refine(x, make_cf, groups, tuned, iters, seed=0, sigma=0.05):
     rng = np.random.default_rng(seed)
-    best = objective(rand, tuned, make_cf(x))
+    best = objective(groups, tuned, make_cf(x))
     for _ in range(iters):
         y = x.copy()
         k = rng.choice(len(x), size=rng.integers(1, 4), replace=False)
         y[k] += rng.normal(0, sigma, size=len(k))
-        j = objective(rand, tuned, make_cf(y))
+        j = objective(groups, tuned, make_cf(y))
         if j < best:
             best, x = j, y
     return x
@@ -163,19 +175,20 @@ def select(dt, path, shapes):
     return [sh for sh in shapes if sh["dt"] == dt and sh["path"] == path]
 
 
-def fit_stage(x0, make_cf, rand, tuned, iters, spread, label):
-    pts = points(rand + tuned)
+def fit_stage(x0, make_cf, rand, paper, tuned, iters, spread, label):
+    pts = points(rand + paper + tuned)
 
     def residuals(x):
         cf = make_cf(x)
         return np.array([w * math.log(cf(sh, t, s) / v) for sh, t, s, v, w in pts])
 
     x = least_squares(residuals, x0, bounds=(x0 - spread, x0 + spread), max_nfev=80).x
-    print("%s: least squares rms %.3f | pick/best %s | built-in shapes %s" % (
-        label, residuals(x).std(), summary(regret(rand, make_cf(x))), summary(regret(tuned, make_cf(x)))), flush=True)
-    x = refine(x, make_cf, rand, tuned, iters)
-    print("%s: refined             | pick/best %s | built-in shapes %s" % (
-        label, summary(regret(rand, make_cf(x))), summary(regret(tuned, make_cf(x)))), flush=True)
+    for stage in ("least squares", "refined"):
+        if stage == "refined":
+            x = refine(x, make_cf, [rand, paper], tuned, iters)
+        print("%s, %s (rms %.3f): pick/best on random shapes %s | paper's sizes %s | built-in shapes %s" % (
+            label, stage, residuals(x).std(), summary(regret(rand, make_cf(x))),
+            summary(regret(paper, make_cf(x))) if paper else "-", summary(regret(tuned, make_cf(x))) if tuned else "-"), flush=True)
     return x
 
 
@@ -183,6 +196,7 @@ def main():
     args = sys.argv[1:]
     iters = 1500
     tuned = []
+    paper = []
     if "--iters" in args:
         i = args.index("--iters")
         iters = int(args[i + 1])
@@ -190,6 +204,10 @@ def main():
     if "--tuned" in args:
         i = args.index("--tuned")
         tuned = load(args[i + 1])
+        del args[i:i + 2]
+    if "--paper" in args:
+        i = args.index("--paper")
+        paper = load(args[i + 1])
         del args[i:i + 2]
     if not args:
         sys.exit(__doc__)
@@ -213,7 +231,8 @@ def main():
     for t in NAMES:
         x0 += [math.log(v) for v in START16[t]] + [0.0]
     x0 = np.array(x0 + [math.log(GLOBALS[k]) for k in GLOBAL_NAMES] + [math.log(2.5)])
-    T16, G, tail16 = unpack16(fit_stage(x0, make16, select("f16", 0, rand), select("f16", 0, tuned), iters, 5.0, "f16 aligned"))
+    T16, G, tail16 = unpack16(fit_stage(x0, make16, select("f16", 0, rand), select("f16", 0, paper), select("f16", 0, tuned), iters,
+                                        5.0, "f16 aligned"))
 
     # binary32, aligned: slab times and tail only (fixed part, HBM efficiency and globals as fitted above)
     def unpack32(x):
@@ -231,7 +250,8 @@ def main():
     for t in NAMES:
         x0 += [math.log(v) for v in START32[t]]
     x0 = np.array(x0 + [math.log(1.5)])
-    T32, tail32 = unpack32(fit_stage(x0, make32, select("f32", 0, rand), select("f32", 0, tuned), iters, 5.0, "f32 aligned"))
+    T32, tail32 = unpack32(fit_stage(x0, make32, select("f32", 0, rand), select("f32", 0, paper), select("f32", 0, tuned), iters,
+                                     5.0, "f32 aligned"))
 
     # misaligned classes: a slab-time multiplier per tile, a factor per number of K-contiguous operands, the tail
     tiles = [t for t in NAMES if t != "k64x64"]
@@ -246,7 +266,7 @@ def main():
             return lambda sh, t, s, sc=(1, 1, 1, 1): cost(t, *T[t], G, sh, s, esz, m[t], floor_lat, tail, lay, sc)
 
         x0 = np.array([math.log(m0)] * 8 + [0.0, 0.0, math.log(tail0)])
-        classes[dt, path] = unpack(fit_stage(x0, make, select(dt, path, rand), select(dt, path, tuned), iters, 3.0,
+        classes[dt, path] = unpack(fit_stage(x0, make, select(dt, path, rand), [], select(dt, path, tuned), iters, 3.0,
                                              "%s path %d" % (dt, path)))
 
     print("\nglobal terms:", {k: float("%.3g" % v) for k, v in G.items()}, "ragged-K tail f16 %.3g f32 %.3g" % (tail16, tail32))

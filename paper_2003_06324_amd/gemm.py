@@ -178,6 +178,16 @@ def tune_save(path, check=True):
     return _check(rc) if check else rc
 
 
+TUNED_TABLE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuned_mi355x.txt")
+
+
+def load_tuned_table():
+    """Loads the picks measured on an MI355X over the paper's size ranges (M, N, K powers of two from 256 to 4096,
+    16-byte aligned operands; written by tune_paper_ranges.py).  Not loaded by default: the cost model answers unless
+    the caller asks for the measured table."""
+    return tune_load(TUNED_TABLE)
+
+
 def tune_load(path, check=True):
     """Adds the picks of a file written by tune_save to the table."""
     rc = load_library().gemm_tune_load(str(path).encode())

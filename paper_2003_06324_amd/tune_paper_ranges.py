@@ -1,0 +1,93 @@
+"""Per-size tuning over the paper's size ranges (Section 5.3: small sizes up to 1024, large sizes 1024..4096,
+powers of two), by the library's own search (gemm_tune): for every M, N, K in {256, 512, 1024, 2048, 4096}, every
+layout pair and both operand types, lets gemm_tune time every configuration, then times the cost model's pick and
+the recorded pick in turn, and writes the table of recorded picks.
+
+    python3 -m paper_2003_06324_amd.tune_paper_ranges [--out picks.txt] [--sizes 256,512,...]
+
+Prints one line per shape and a summary (time of the model's pick over time of the tuned pick).  The table it
+writes is what paper_2003_06324_amd/tuned_mi355x.txt holds; load it with gemm.tune_load() (the library does not
+load it by itself: the cost model is the default, this is the measured alternative for these sizes).
+"""
+import itertools
+import os
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def main():
+    import torch
+    import gemm_inputs as gi
+    import paper_2003_06324_amd as g
+
+    args = sys.argv[1:]
+    out = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuned_mi355x.txt")
+    sizes = [256, 512, 1024, 2048, 4096]
+    if "--out" in args:
+        out = args[args.index("--out") + 1]
+    if "--sizes" in args:
+        sizes = [int(x) for x in args[args.index("--sizes") + 1].split(",")]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, iters):
+        for _ in range(30):     # the part's clock rises over the first tens of microseconds of work
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3  # microseconds
+
+    g.force_config(None)
+    g.tune_clear()
+    ratios = {"f16": [], "f32": []}
+    changed = 0
+    big = max(sizes)
+    bufs = {}
+    for dt, tdt, kind, call in (("f16", torch.float16, g.KIND_F16F32, g.gemm_f16f32), ("f32", torch.float32, g.KIND_F32, g.gemm_f32)):
+        # one pair of operand buffers of the largest size serves every shape (packed leading dimensions)
+        bufs[dt] = (torch.randn(big * big, device="cuda", dtype=tdt), torch.randn(big * big, device="cuda", dtype=tdt),
+                    torch.empty(big * big, device="cuda", dtype=torch.float32))
+        A, B, C = bufs[dt]
+        for M, N, K in itertools.product(sizes, repeat=3):
+            iters = 20 if 2.0 * M * N * K > 5e10 else 100
+            for lay in ("NN", "NT", "TN", "TT"):
+                la, lb = gi.LAYOUTS[lay]
+                fn = lambda: call(M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
+                fn()
+                model = g.last_config().split()
+                model = model[1] + ":" + model[4]
+                pick = g.tune(kind, M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
+                # both picks forced in turn, twice, the better take of each: the part's clock takes a millisecond to
+                # settle after the host has waited for the GPU, and whichever is timed first would pay for it
+                t_model = t_tuned = float("inf")
+                for _ in range(2):
+                    g.force_config(model)
+                    t_model = min(t_model, timed(fn, iters))
+                    g.force_config(pick)
+                    t_tuned = min(t_tuned, timed(fn, iters))
+                g.force_config(None)
+                if pick == model:
+                    t_model = t_tuned = min(t_model, t_tuned)
+                else:
+                    changed += 1
+                ratios[dt].append(t_model / t_tuned)
+                print("%s %dx%dx%d %s: model %s %.1f us | tuned %s %.1f us | model/tuned %.2f" % (
+                    dt, M, N, K, lay, model, t_model, pick, t_tuned, t_model / t_tuned), flush=True)
+    g.tune_save(out)
+    for dt, r in ratios.items():
+        r = np.array(r)
+        print("%s: %d shapes, model/tuned geometric mean %.3f, median %.2f, 90th percentile %.2f, worst %.2f" % (
+            dt, len(r), float(np.exp(np.log(r).mean())), float(np.median(r)), float(np.quantile(r, 0.9)), float(r.max())))
+    print("%d of %d picks differ from the model's; table written to %s" % (changed, sum(len(r) for r in ratios.values()), out))
+    g.tune_clear()
+
+
+if __name__ == "__main__":
+    main()
