@@ -219,7 +219,8 @@ int gemm_tune_clear(void);
  * granules, tile name, K slices; '#' starts a comment line); gemm_tune_load adds the pairs of such a file to
  * the table, replacing entries for the same class.  Host only.  GEMM_ERR_INVALID_ARG if the file cannot be
  * opened or written, or (load) if any line does not parse, names a tile this build does not have or one
- * that cannot serve the line's class: then nothing of the file is taken over.
+ * that cannot serve the line's class, or a K-slice count outside 1 .. 32 (what gemm_tune records): then
+ * nothing of the file is taken over.
  */
 int gemm_tune_save(const char *path);
 int gemm_tune_load(const char *path);

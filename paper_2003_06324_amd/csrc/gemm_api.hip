@@ -794,7 +794,7 @@ int gemm_tune_load(const char *path)
         char name[32];
         if (sscanf(line, "%d %lld %lld %lld %d %d %d %d %31s %d", &esz, &M, &N, &K, &path_, &kc, &cus, &whole, name, &slices) != 10 ||
             (esz != 2 && esz != 4) || M <= 0 || N <= 0 || K <= 0 || path_ < 0 || path_ > 3 || kc < 0 || kc > 2 || cus <= 0 ||
-            (whole != 0 && whole != 1) || slices < 1 || slices > 1024) {
+            (whole != 0 && whole != 1) || slices < 1 || slices > 32) {   // gemm_tune records 1 .. 32 slices
             rc = GEMM_ERR_INVALID_ARG;
             break;
         }

@@ -152,11 +152,12 @@ def test_recorded_picks_load_from_a_file_and_precede_the_cost_model(tmp_path):
         assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR) == model
         g.tune_load(out)
         assert g.query_config(2, 2048, 2048, 2048, 16, g.ROW_MAJOR, g.COL_MAJOR) == "t64x128:s4"
-        # files that do not parse, name an unknown tile, or give the K-split-across-waves tile a class it does not
-        # serve are refused as a whole
+        # files that do not parse, name an unknown tile, give the K-split-across-waves tile a class it does not
+        # serve, or a slice count the tuner never records are refused as a whole
         g.tune_clear()
         for text in ("2 2048 2048 2048 0 2 256 1 t64x128\n", "2 64 64 64 0 2 256 1 t1x1 1\n", "3 64 64 64 0 2 256 1 t64x64 1\n",
-                     "2 512 512 512 0 2 256 1 t64x64 1\n2 64 64 100 0 2 256 0 k64x64 1\n", "2 64 64 64 7 2 256 1 t64x64 1\n"):
+                     "2 512 512 512 0 2 256 1 t64x64 1\n2 64 64 100 0 2 256 0 k64x64 1\n", "2 64 64 64 7 2 256 1 t64x64 1\n",
+                     "2 4096 4096 8192 0 2 256 1 t64x64 64\n", "2 64 64 64 0 2 256 1 t64x64 0\n"):
             f.write_text(text)
             assert g.tune_load(f, check=False) == -1, text
         out2 = tmp_path / "empty.txt"
