@@ -191,8 +191,9 @@ int gemm_cost_model_scale(int term, double factor);
  * point's: the call computes C = A * B like it, then runs the product again with each candidate
  * (tile, K slices) pair -- the max_candidates cheapest by the cost model, or every pair the library
  * has if max_candidates is 0 (9 tiles x up to 6 slice counts; about 10 ms for a mid-size shape) --
- * timing each with events on hip_stream (after a warm-up of 40 launches: two untimed and six timed launches per
- * pair, then the four fastest again with 24 timed launches each), records the fastest in a process-wide table, computes C
+ * timing each with events on hip_stream (two untimed and six timed launches per pair behind 40 untimed ones, all
+ * enqueued back to back; then the four fastest and the cost model's own pick again, twice in turn with 24 timed
+ * launches each, the better take of each kept), records the fastest in a process-wide table, computes C
  * once more with it and writes "<tile>:s<slices>" into buf.  Later calls with the same M, N, K,
  * operand width (16-bit or binary32), layouts and alignment class on a device with as many CUs use
  * the recorded pair (so do gemm_query_config*); a forced configuration still overrides it, and

@@ -1,7 +1,7 @@
 """Per-size tuning over the paper's size ranges (Section 5.3: small sizes up to 1024, large sizes 1024..4096,
 powers of two), by the library's own search (gemm_tune): for every M, N, K in {256, 512, 1024, 2048, 4096}, every
 layout pair and both operand types, lets gemm_tune time every configuration, then times the cost model's pick and
-the recorded pick in turn, and writes the table of recorded picks.
+the recorded pick alternately in one pass, and writes the table of recorded picks.
 
     python3 -m paper_2003_06324_amd.tune_paper_ranges [--out picks.txt] [--sizes 256,512,...]
     python3 -m paper_2003_06324_amd.tune_paper_ranges --shapes-file paper_2003_06324_amd/tune_shapes/validation.txt --out /tmp/picks.txt
@@ -41,17 +41,28 @@ def main():
                 listed.append((f[0], int(f[1]), int(f[2]), int(f[3]), f[4], int(f[5]) if len(f) > 5 else 0))
     stream = torch.cuda.current_stream().cuda_stream
 
-    def timed(fn, iters):
-        for _ in range(30):     # the part's clock rises over the first tens of microseconds of work
+    def timed(fn, configs, iters):
+        """Microseconds per call under each forced configuration of `configs`, in one pass: 30 launches of the automatic
+        choice, then per configuration 3 untimed and `iters` timed launches between two events, everything enqueued back
+        to back and one wait at the end (the part lowers its clock within microseconds of idling; a wait between
+        configurations would time the next one on a rising clock)."""
+        g.force_config(None)
+        for _ in range(30):
             fn()
+        pairs = []
+        for cfg in configs:
+            g.force_config(cfg)
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            pairs.append((e0, e1))
+        g.force_config(None)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters * 1e3  # microseconds
+        return [e0.elapsed_time(e1) / iters * 1e3 for e0, e1 in pairs]
 
     g.force_config(None)
     g.tune_clear()
@@ -79,15 +90,9 @@ def main():
                 model = g.last_config().split()
                 model = model[1] + ":" + model[4]
                 pick = g.tune(kind, M, N, K, A, la, 0, B, lb, 0, C, gi.ROW_MAJOR, 0, stream)
-                # both picks forced in turn, twice, the better take of each: the part's clock takes a millisecond to
-                # settle after the host has waited for the GPU, and whichever is timed first would pay for it
-                t_model = t_tuned = float("inf")
-                for _ in range(2):
-                    g.force_config(model)
-                    t_model = min(t_model, timed(fn, iters))
-                    g.force_config(pick)
-                    t_tuned = min(t_tuned, timed(fn, iters))
-                g.force_config(None)
+                # both picks forced alternately in one pass, the better take of each
+                takes = timed(fn, [model, pick, model, pick], iters)
+                t_model, t_tuned = min(takes[0::2]), min(takes[1::2])
                 if pick == model:
                     t_model = t_tuned = min(t_model, t_tuned)
                 else:
