@@ -97,8 +97,7 @@ def config_rows(per_layout, S, skip_big):
             for _ in range(20):
                 fn(*call, stream.cuda_stream)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(8)]
-            torch.cuda.synchronize()
-            ev[0].record(stream)
+            ev[0].record(stream)   # no host wait after the warm-up: the part would drop its clock in the gap
             for b in range(7):
                 for _ in range(iters):
                     fn(*call, stream.cuda_stream)
