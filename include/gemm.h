@@ -190,7 +190,7 @@ int gemm_cost_model_scale(int term, double factor);
  * call performs it).  kind names the entry point (GEMM_KIND_*), the other arguments are that entry
  * point's: the call computes C = A * B like it, then runs the product again with each candidate
  * (tile, K slices) pair -- the max_candidates cheapest by the cost model, or every pair the library
- * has if max_candidates is 0 (9 tiles x up to 6 slice counts; about 10 ms for a mid-size shape) --
+ * has if max_candidates is 0 (9 tiles x up to 6 slice counts; 10-50 ms for a mid-size shape, 1.3 s at 8192^3) --
  * timing each with events on hip_stream (two untimed and six timed launches per pair behind 40 untimed ones, all
  * enqueued back to back; then the four fastest and the cost model's own pick again, twice in turn with 24 timed
  * launches each, the better take of each kept), records the fastest in a process-wide table, computes C
